@@ -1,0 +1,171 @@
+/*
+ * striped_attn.h - C ABI of the MI355X (gfx950) ring-step library for Striped
+ * Attention (arxiv 2311.09431) and the contiguous Ring Attention layout it is
+ * compared with.
+ *
+ * Conventions common to every entry point
+ *  - All tensor pointers are DEVICE pointers unless a parameter says "host".
+ *    The caller owns every buffer; the library allocates no device memory.
+ *  - Q/K/V/dO/O/dQ/dK/dV are laid out [B, H, rows, d] with d contiguous and
+ *    consecutive rows d elements apart; batch and head strides are given in
+ *    elements.  A device's shard of c rows is a row offset into such a tensor.
+ *    LSE and delta are [B, H, rows] fp32 with their own batch/head strides.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls only enqueue work; they do not synchronise, except sa_ring_fwd /
+ *    sa_ring_bwd when asked for per-step timings.
+ *  - Return value: SA_OK (0) or a negative sa_status.  On any error nothing
+ *    has been launched.  No entry point throws.
+ *  - Pointers must be aligned to 16 bytes (permutes: to min(16, inner_bytes
+ *    rounded down to a power of two)).
+ *  - Notation follows the paper: N devices, block size c = n_seq / N, query
+ *    device j = q_dev, key/value device k = kv_dev.
+ */
+#ifndef STRIPED_ATTN_H
+#define STRIPED_ATTN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SA_OK = 0,
+    SA_ERR_NULL = -1,    /* a required pointer is NULL */
+    SA_ERR_SHAPE = -2,   /* non-positive size, n_seq % N != 0, unsupported d, bad stride */
+    SA_ERR_DEV = -3,     /* q_dev or kv_dev outside [0, N) or N < 1 */
+    SA_ERR_DTYPE = -4,   /* dtype not SA_F32 / SA_BF16 */
+    SA_ERR_LAYOUT = -5,  /* layout not SA_CONTIGUOUS / SA_STRIPED, or src == dst in a permute */
+    SA_ERR_ALIGN = -6,   /* pointer or stride not aligned as required */
+    SA_ERR_HIP = -7      /* a HIP call failed (the HIP error is left pending) */
+} sa_status;
+
+typedef enum { SA_CONTIGUOUS = 0, SA_STRIPED = 1 } sa_layout;
+typedef enum { SA_F32 = 0, SA_BF16 = 1 } sa_dtype;
+
+/* Shape of one device's shard as seen by a ring step. */
+typedef struct {
+    int32_t B, H;          /* batch, heads */
+    int32_t c;             /* rows per device (block size) */
+    int32_t d;             /* head dimension: any 1..256 (multiple of 4 for fp32, 8 for bf16);
+                              bf16 with d = 128 and c % 128 == 0 takes the MFMA kernels */
+    int64_t stride_b;      /* elements between batches in Q/K/V/dO/O/dQ/dK/dV */
+    int64_t stride_h;      /* elements between heads in the same tensors */
+    int64_t stat_stride_b; /* elements between batches in LSE / delta */
+    int64_t stat_stride_h; /* elements between heads in LSE / delta */
+    int32_t dtype;         /* sa_dtype of Q/K/V/dO (O, LSE, delta, dQ, dK, dV are fp32) */
+    float softmax_scale;   /* multiplies q.k inside the softmax; <= 0 selects 1/sqrt(d) */
+} sa_shape;
+
+/*
+ * Stripe permutation (Sec. 2.3: token t goes to device t mod N; realised as a
+ * permutation followed by a contiguous split).  src and dst are [outer, n_seq,
+ * inner_bytes] byte arrays; dst[o, (t mod N) * c + t div N, :] = src[o, t, :]
+ * with c = n_seq / N.  Serves Q/K/V rows as well as token ids, position ids and
+ * targets.  Bit-exact byte movement.  src and dst must not overlap.
+ * Errors: NULL, n_seq % N != 0 or sizes <= 0 (SHAPE), N < 1 (DEV), src == dst
+ * (LAYOUT), misalignment (ALIGN).
+ */
+int sa_stripe_permute(const void* src, void* dst, int64_t outer, int64_t n_seq,
+                      int64_t inner_bytes, int32_t N, void* stream);
+
+/* Inverse of sa_stripe_permute: dst[o, t, :] = src[o, (t mod N) * c + t div N, :]. */
+int sa_unstripe_permute(const void* src, void* dst, int64_t outer, int64_t n_seq,
+                        int64_t inner_bytes, int32_t N, void* stream);
+
+/*
+ * Initialise a device's output accumulator (Algorithm 1, first line): O = 0,
+ * LSE = -inf.  o is fp32 [B, H, c, d], lse fp32 [B, H, c], strides from `shape`.
+ */
+int sa_state_init(float* o, float* lse, const sa_shape* shape, void* stream);
+
+/*
+ * One ring step, forward (Algorithm 1, AccumulateAttentionFragment): the c query
+ * rows of device q_dev attend to the c key/value rows of device kv_dev under
+ * GetMask(q_dev, kv_dev) and the result is folded into the running (o, lse):
+ *   lse' = log(exp(lse) + sum_allowed exp(scale q.k)),
+ *   o'   = (exp(lse - lse') o + sum_allowed exp(scale q.k - lse') v).
+ * The mask is causal in the ORIGINAL token order (Sec. 2.1, 2.3).  With local
+ * rows a (query) and b (key): contiguous layout (Sec. 2.2): q_dev < kv_dev
+ * nothing allowed (no launch), q_dev == kv_dev allowed iff b <= a, q_dev >
+ * kv_dev everything allowed; striped layout (Sec. 2.3): kv_dev <= q_dev allowed
+ * iff b <= a, kv_dev > q_dev allowed iff b < a.  Tiles without an allowed pair
+ * are skipped (Sec. 2.2.1).
+ * q, k, v: shard pointers of dtype shape->dtype; o, lse: fp32, read and written.
+ * Rows that see no key keep their state (o = 0, lse = -inf if never touched).
+ */
+int sa_attn_step_fwd(const void* q, const void* k, const void* v, float* o, float* lse,
+                     int32_t q_dev, int32_t kv_dev, int32_t N, int32_t layout,
+                     const sa_shape* shape, void* stream);
+
+/*
+ * End of the ring (Algorithm 1, "normalize"): the running o is kept normalised,
+ * so this only rounds fp32 o to `shape->dtype` into `out` (same strides).
+ */
+int sa_finalize(const float* o, void* out, const sa_shape* shape, void* stream);
+
+/*
+ * Backward preprocessing: delta[b, h, a] = sum_t dout[b, h, a, t] * o[b, h, a, t]
+ * with the FINAL fp32 o of the forward ring.  (The paper gives no backward
+ * pass; this and sa_attn_step_bwd are the analytic gradient of Sec. 2.1.)
+ */
+int sa_bwd_preprocess(const float* o, const void* dout, float* delta, const sa_shape* shape,
+                      void* stream);
+
+/*
+ * One ring step, backward.  With P = exp(scale q.k - lse) on the allowed pairs of
+ * GetMask(q_dev, kv_dev) (same rule as the forward step; lse and delta are the
+ * FINAL values for device q_dev's rows):
+ *   dv += P^T dout,  dS = P * (dout v^T - delta),  dq += scale dS k,  dk += scale dS^T q.
+ * dq (rows of q_dev), dk, dv (rows of kv_dev) are fp32 accumulators, read and
+ * written; the caller zeroes them before the first step.
+ */
+int sa_attn_step_bwd(const void* q, const void* k, const void* v, const void* dout,
+                     const float* lse, const float* delta, float* dq, float* dk, float* dv,
+                     int32_t q_dev, int32_t kv_dev, int32_t N, int32_t layout,
+                     const sa_shape* shape, void* stream);
+
+/*
+ * Ring driver, forward (Algorithm 1 played on one GPU): for round i = 0..N-1 and
+ * device j = 0..N-1, k = (j - i) mod N, run sa_attn_step_fwd on shard j of Q/O/LSE
+ * and shard k of K/V.  Q, K, V, O are full [B, H, N*c, d] tensors in device order
+ * (stripe-permuted for SA_STRIPED), LSE is [B, H, N*c]; `shape` describes one
+ * shard (c rows) and the strides of the full tensors.  O and LSE are initialised
+ * here.  q_dev_only >= 0 plays only that device's N steps (one device's share).
+ * step_ms: NULL, or a HOST array of N*N floats receiving the duration of step
+ * (round i, device j) at [i*N + j] in milliseconds (steps not played: 0); when
+ * non-NULL the call synchronises the stream before returning.
+ */
+int sa_ring_fwd(const void* Q, const void* K, const void* V, float* O, float* LSE, int32_t N,
+                int32_t layout, const sa_shape* shape, int32_t q_dev_only, float* step_ms,
+                void* stream);
+
+/*
+ * Ring driver, backward: delta = rowsum(dO * O) for the played devices, then the
+ * same schedule calling sa_attn_step_bwd.  dQ, dK, dV are full fp32 tensors,
+ * zeroed here.  With q_dev_only >= 0 only that device's steps are played (dQ is
+ * then complete for that device; dK/dV hold only its contributions).
+ */
+int sa_ring_bwd(const void* Q, const void* K, const void* V, const void* dO, const float* O,
+                const float* LSE, float* delta, float* dQ, float* dK, float* dV, int32_t N,
+                int32_t layout, const sa_shape* shape, int32_t q_dev_only, float* step_ms,
+                void* stream);
+
+/*
+ * Host-only helpers (no GPU work).
+ * sa_mask_offset: the step's mask as "allowed iff b <= a - off": returns 0 and
+ * writes *off (0 or 1), or writes *kind = 0 empty / 1 triangular / 2 full.
+ * sa_step_pairs: number of allowed (query, key) pairs of the step, i.e. Work(j, k)
+ * of Sec. 2.3 for the striped layout and c^2 / c(c+1)/2 / 0 for the contiguous one.
+ */
+int sa_step_mask(int32_t q_dev, int32_t kv_dev, int32_t N, int32_t layout, int32_t* kind,
+                 int32_t* off);
+int64_t sa_step_pairs(int32_t q_dev, int32_t kv_dev, int32_t N, int32_t layout, int64_t c);
+
+/* Human-readable name of a status code; never NULL. */
+const char* sa_status_str(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STRIPED_ATTN_H */

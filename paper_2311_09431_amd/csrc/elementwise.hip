@@ -1,0 +1,138 @@
+// Bandwidth-bound helpers around the ring step: accumulator initialisation
+// (Algorithm 1, first line), the final cast (Algorithm 1, "normalize": the running
+// output is kept normalised, so only a rounding is left) and the backward
+// preprocessing delta = rowsum(dO * O).
+#include <hip/hip_bf16.h>
+
+#include "sa_internal.h"
+
+namespace sa {
+
+// grid: (row blocks, B*H); each thread handles 4 floats of a row.
+__global__ void __launch_bounds__(256)
+state_init_kernel(float* __restrict__ o, float* __restrict__ lse, int H, int c, int d,
+                  int64_t sb, int64_t sh, int64_t ssb, int64_t ssh, float lse_value, bool touch_lse) {
+    const int bh = blockIdx.y, b = bh / H, h = bh - b * H;
+    float* ob = o + b * sb + h * sh;
+    const int64_t n4 = (int64_t)c * d / 4;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256)
+        reinterpret_cast<float4*>(ob)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (touch_lse) {
+        float* lb = lse + b * ssb + h * ssh;
+        for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < c; i += (int64_t)gridDim.x * 256)
+            lb[i] = lse_value;
+    }
+}
+
+static unsigned row_blocks(int64_t work_items) {
+    int64_t g = (work_items + 255) / 256;
+    if (g > 4096) g = 4096;
+    if (g < 1) g = 1;
+    return (unsigned)g;
+}
+
+hipError_t launch_state_init(float* o, float* lse, const sa_shape& s, hipStream_t st) {
+    dim3 grid(row_blocks((int64_t)s.c * s.d / 4), s.B * s.H);
+    hipLaunchKernelGGL(state_init_kernel, grid, dim3(256), 0, st, o, lse, s.H, s.c, s.d, s.stride_b,
+                       s.stride_h, s.stat_stride_b, s.stat_stride_h, -INFINITY, true);
+    return hipGetLastError();
+}
+
+hipError_t launch_zero_f32(float* p, const sa_shape& s, hipStream_t st) {
+    dim3 grid(row_blocks((int64_t)s.c * s.d / 4), s.B * s.H);
+    hipLaunchKernelGGL(state_init_kernel, grid, dim3(256), 0, st, p, (float*)nullptr, s.H, s.c, s.d,
+                       s.stride_b, s.stride_h, (int64_t)0, (int64_t)0, 0.f, false);
+    return hipGetLastError();
+}
+
+template <typename OutT>
+__device__ inline void store4(OutT* p, float4 v);
+template <>
+__device__ inline void store4<float>(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
+template <>
+__device__ inline void store4<__hip_bfloat16>(__hip_bfloat16* p, float4 v) {
+    __hip_bfloat16 t[4] = {__float2bfloat16(v.x), __float2bfloat16(v.y), __float2bfloat16(v.z),
+                           __float2bfloat16(v.w)};
+    *reinterpret_cast<uint2*>(p) = *reinterpret_cast<uint2*>(t);
+}
+
+template <typename OutT>
+__global__ void __launch_bounds__(256)
+finalize_kernel(const float* __restrict__ o, OutT* __restrict__ out, int H, int c, int d, int64_t sb,
+                int64_t sh) {
+    const int bh = blockIdx.y, b = bh / H, h = bh - b * H;
+    const float* ob = o + b * sb + h * sh;
+    OutT* yb = out + b * sb + h * sh;
+    const int64_t n4 = (int64_t)c * d / 4;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256)
+        store4<OutT>(yb + i * 4, reinterpret_cast<const float4*>(ob)[i]);
+}
+
+hipError_t launch_finalize(const float* o, void* out, const sa_shape& s, hipStream_t st) {
+    dim3 grid(row_blocks((int64_t)s.c * s.d / 4), s.B * s.H);
+    if (s.dtype == SA_F32)
+        hipLaunchKernelGGL(finalize_kernel<float>, grid, dim3(256), 0, st, o, (float*)out, s.H, s.c,
+                           s.d, s.stride_b, s.stride_h);
+    else
+        hipLaunchKernelGGL(finalize_kernel<__hip_bfloat16>, grid, dim3(256), 0, st, o,
+                           (__hip_bfloat16*)out, s.H, s.c, s.d, s.stride_b, s.stride_h);
+    return hipGetLastError();
+}
+
+template <typename T>
+__device__ inline float4 load4(const T* p);
+template <>
+__device__ inline float4 load4<float>(const float* p) { return *reinterpret_cast<const float4*>(p); }
+template <>
+__device__ inline float4 load4<__hip_bfloat16>(const __hip_bfloat16* p) {
+    uint2 raw = *reinterpret_cast<const uint2*>(p);
+    float4 r;
+    r.x = __uint_as_float(raw.x << 16);
+    r.y = __uint_as_float(raw.x & 0xffff0000u);
+    r.z = __uint_as_float(raw.y << 16);
+    r.w = __uint_as_float(raw.y & 0xffff0000u);
+    return r;
+}
+
+// One 16-lane group per row (d/4 <= 64 float4 per row, strided over the group);
+// a 256-thread block covers 16 rows.
+template <typename T>
+__global__ void __launch_bounds__(256)
+bwd_preprocess_kernel(const float* __restrict__ o, const T* __restrict__ dout, float* __restrict__ delta,
+                      int H, int c, int d, int64_t sb, int64_t sh, int64_t ssb, int64_t ssh) {
+    const int bh = blockIdx.y, b = bh / H, h = bh - b * H;
+    const int g = threadIdx.x >> 4, l = threadIdx.x & 15;
+    for (int64_t row = (int64_t)blockIdx.x * 16 + g; row < c; row += (int64_t)gridDim.x * 16) {
+        const float* orow = o + b * sb + h * sh + row * d;
+        const T* grow = dout + b * sb + h * sh + row * d;
+        float acc = 0.f;
+        for (int t = l * 4; t < d; t += 64) {
+            float4 x = *reinterpret_cast<const float4*>(orow + t);
+            float4 y = load4<T>(grow + t);
+            acc += x.x * y.x + x.y * y.y + x.z * y.z + x.w * y.w;
+        }
+        acc += __shfl_xor(acc, 8, 16);
+        acc += __shfl_xor(acc, 4, 16);
+        acc += __shfl_xor(acc, 2, 16);
+        acc += __shfl_xor(acc, 1, 16);
+        if (l == 0) delta[b * ssb + h * ssh + row] = acc;
+    }
+}
+
+hipError_t launch_bwd_preprocess(const float* o, const void* dout, float* delta, const sa_shape& s,
+                                 hipStream_t st) {
+    int64_t g = ((int64_t)s.c + 15) / 16;
+    if (g > 8192) g = 8192;
+    dim3 grid((unsigned)g, s.B * s.H);
+    if (s.dtype == SA_F32)
+        hipLaunchKernelGGL(bwd_preprocess_kernel<float>, grid, dim3(256), 0, st, o, (const float*)dout,
+                           delta, s.H, s.c, s.d, s.stride_b, s.stride_h, s.stat_stride_b,
+                           s.stat_stride_h);
+    else
+        hipLaunchKernelGGL(bwd_preprocess_kernel<__hip_bfloat16>, grid, dim3(256), 0, st, o,
+                           (const __hip_bfloat16*)dout, delta, s.H, s.c, s.d, s.stride_b, s.stride_h,
+                           s.stat_stride_b, s.stat_stride_h);
+    return hipGetLastError();
+}
+
+}  // namespace sa

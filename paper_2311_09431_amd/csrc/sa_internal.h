@@ -1,0 +1,49 @@
+// Internal declarations shared by the HIP translation units of libstriped_attn.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "striped_attn.h"
+
+namespace sa {
+
+// Mask of one ring step in local indices: key b is allowed for query a iff
+// b <= a - off (kind == TRI) or always (kind == FULL).  Derived from the
+// original token positions: striped a*N + dev, contiguous dev*c + a.
+enum MaskKind : int { MASK_EMPTY = 0, MASK_TRI = 1, MASK_FULL = 2 };
+
+struct StepArgs {
+    const void* q;
+    const void* k;
+    const void* v;
+    const void* dout;     // backward only
+    float* o;             // forward: running output
+    float* lse;           // forward: running log-sum-exp; backward: final (read-only)
+    const float* delta;   // backward only
+    float* dq;
+    float* dk;
+    float* dv;
+    int B, H, c, d;
+    int64_t stride_b, stride_h, stat_stride_b, stat_stride_h;
+    float scale;
+    int kind;             // MaskKind (never MASK_EMPTY at launch)
+    int off;              // 0 or 1 when kind == MASK_TRI
+};
+
+// launchers: return hipSuccess or the launch error
+hipError_t launch_permute(const void* src, void* dst, int64_t outer, int64_t n_seq,
+                          int64_t inner_bytes, int N, bool inverse, hipStream_t st);
+hipError_t launch_state_init(float* o, float* lse, const sa_shape& s, hipStream_t st);
+hipError_t launch_finalize(const float* o, void* out, const sa_shape& s, hipStream_t st);
+hipError_t launch_bwd_preprocess(const float* o, const void* dout, float* delta,
+                                 const sa_shape& s, hipStream_t st);
+hipError_t launch_zero_f32(float* p, const sa_shape& s, hipStream_t st);
+
+hipError_t launch_fwd_generic(const StepArgs& a, int dtype, hipStream_t st);
+hipError_t launch_bwd_generic(const StepArgs& a, int dtype, hipStream_t st);
+bool fwd_mfma_supported(const StepArgs& a, int dtype);
+hipError_t launch_fwd_mfma(const StepArgs& a, hipStream_t st);
+bool bwd_mfma_supported(const StepArgs& a, int dtype);
+hipError_t launch_bwd_mfma(const StepArgs& a, hipStream_t st);
+
+}  // namespace sa

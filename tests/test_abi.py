@@ -1,0 +1,110 @@
+"""Host-side checks of the C ABI: the library loads, exports every symbol the
+header declares, classifies steps like the oracle, and rejects bad arguments
+before launching anything (fake non-null pointers; no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from oracle import striped_attention as orc
+from paper_2311_09431_amd import binding as sa
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    with open(os.path.join(ROOT, "include", "striped_attn.h")) as f:
+        text = f.read()
+    declared = set(re.findall(r"\b(sa_[a-z_]+)\s*\(", text))
+    assert declared == set(sa.EXPORTS)
+    L = sa.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+@pytest.mark.parametrize("N,c", [(4, 4), (8, 3), (1, 5)])
+def test_step_mask_and_pairs_match_the_oracle(N, c):
+    import numpy as np
+    for layout in (sa.CONTIGUOUS, sa.STRIPED):
+        for j in range(N):
+            for k in range(N):
+                kind, off = sa.sa_step_mask(j, k, N, layout)
+                allowed = orc.get_mask(j, k, N, c, layout)
+                a = np.arange(c)[:, None]
+                b = np.arange(c)[None, :]
+                if kind == sa.MASK_EMPTY:
+                    mine = np.zeros((c, c), bool)
+                elif kind == sa.MASK_FULL:
+                    mine = np.ones((c, c), bool)
+                else:
+                    mine = b <= a - off
+                assert (mine == allowed).all()
+                assert sa.sa_step_pairs(j, k, N, layout, c) == orc.work(j, k, N, c, layout)
+
+
+def _shape(**kw):
+    base = dict(B=1, H=2, c=64, d=64, stride_b=2 * 256 * 64, stride_h=256 * 64, stat_stride_b=512,
+                stat_stride_h=256, dtype=sa.F32, softmax_scale=0.0)
+    base.update(kw)
+    return sa.SaShape(**base)
+
+
+def test_argument_errors_are_reported_before_any_launch():
+    L = sa.lib()
+    p = ctypes.c_void_p(0x1000)      # non-null, 16-byte aligned, never dereferenced on error paths
+    odd = ctypes.c_void_p(0x1004)
+    null = ctypes.c_void_p(0)
+    ok = _shape()
+    f = L.sa_attn_step_fwd
+    assert f(null, p, p, p, p, 0, 0, 4, 0, ctypes.byref(ok), None) == -1
+    assert f(p, p, p, p, p, 0, 0, 4, 0, None, None) == -1
+    assert f(p, p, p, p, p, 4, 0, 4, 0, ctypes.byref(ok), None) == -3
+    assert f(p, p, p, p, p, 0, -1, 4, 0, ctypes.byref(ok), None) == -3
+    assert f(p, p, p, p, p, 0, 0, 0, 0, ctypes.byref(ok), None) == -3
+    assert f(p, p, p, p, p, 0, 0, 4, 2, ctypes.byref(ok), None) == -5
+    assert f(p, odd, p, p, p, 0, 0, 4, 0, ctypes.byref(ok), None) == -6
+    assert f(p, p, p, p, p, 0, 0, 4, 0, ctypes.byref(_shape(dtype=7)), None) == -4
+    assert f(p, p, p, p, p, 0, 0, 4, 0, ctypes.byref(_shape(d=0)), None) == -2
+    assert f(p, p, p, p, p, 0, 0, 4, 0, ctypes.byref(_shape(d=512)), None) == -2
+    assert f(p, p, p, p, p, 0, 0, 4, 0, ctypes.byref(_shape(d=66)), None) == -2
+    assert f(p, p, p, p, p, 0, 0, 4, 0, ctypes.byref(_shape(c=0)), None) == -2
+    assert f(p, p, p, p, p, 0, 0, 4, 0, ctypes.byref(_shape(stride_h=10)), None) == -2
+    assert f(p, p, p, p, p, 0, 0, 4, 0, ctypes.byref(_shape(dtype=sa.BF16, stride_h=256 * 64 + 4)),
+             None) == -6
+    # an entirely masked contiguous step is a no-op that succeeds without a launch
+    assert f(p, p, p, p, p, 0, 1, 4, sa.CONTIGUOUS, ctypes.byref(ok), None) == 0
+
+    g = L.sa_stripe_permute
+    assert g(null, p, 1, 16, 4, 4, None) == -1
+    assert g(p, p, 1, 16, 4, 4, None) == -5
+    assert g(p, odd, 1, 16, 8, 4, None) == -6
+    assert g(p, ctypes.c_void_p(0x2000), 1, 18, 4, 4, None) == -2
+    assert g(p, ctypes.c_void_p(0x2000), 1, 16, 0, 4, None) == -2
+    assert g(p, ctypes.c_void_p(0x2000), 1, 16, 4, 0, None) == -3
+    assert L.sa_unstripe_permute(p, ctypes.c_void_p(0x2000), 1, 18, 4, 4, None) == -2
+
+    b = L.sa_attn_step_bwd
+    assert b(p, p, p, p, p, p, p, p, null, 0, 0, 4, 0, ctypes.byref(ok), None) == -1
+    assert b(p, p, p, p, p, p, p, p, p, 0, 9, 4, 0, ctypes.byref(ok), None) == -3
+
+    r = L.sa_ring_fwd
+    assert r(p, p, p, p, p, 4, 1, ctypes.byref(ok), 4, None, None) == -3
+    assert r(p, p, p, p, p, 8, 1, ctypes.byref(ok), -1, None, None) == -2   # strides hold only 4 shards
+    assert L.sa_state_init(p, null, ctypes.byref(ok), None) == -1
+    assert L.sa_finalize(p, odd, ctypes.byref(ok), None) == -6
+    assert L.sa_bwd_preprocess(p, p, null, ctypes.byref(ok), None) == -1
+
+
+def test_status_strings():
+    assert sa.sa_status_str(0) == "ok"
+    assert "shape" in sa.sa_status_str(-2)
+    assert sa.sa_status_str(-99) == "unknown status"
+    assert sa.sa_step_pairs(0, 9, 4, 0, 8) == -1
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    x = torch.zeros(1, 1, 8, 4)
+    with pytest.raises(TypeError):
+        sa.sa_stripe_permute(x, x.clone(), 2)

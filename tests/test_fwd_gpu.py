@@ -1,0 +1,105 @@
+"""GPU parity of the forward ring step against the fp64 oracle (full causal
+attention of the unpermuted sequence), through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import striped_attention as orc
+from paper_2311_09431_amd import binding as sa
+from paper_2311_09431_amd import inputs
+from tests import helpers as hp
+
+pytestmark = pytest.mark.gpu
+
+# tolerances: fp32 configuration 1e-5 on O and LSE; bf16 inputs with fp32
+# accumulation 2e-2 on O and 1e-3 on LSE
+TOL = {torch.float32: (1e-5, 1e-5), torch.bfloat16: (2e-2, 1e-3)}
+
+
+def _check_ring(B, H, S, d, N, layout, dtype, seed, scale=None, use_driver=False, order=None):
+    Q, K, V = inputs.qkv(B, H, S, d, seed, dtype)
+    sc = scale if scale else 1.0 / np.sqrt(d)
+    O, LSE = hp.ring_forward_gpu(Q.cuda(), K.cuda(), V.cuda(), N, layout, scale, use_driver, order)
+    torch.cuda.synchronize()
+    Oh = hp.from_device_order_host(O.cpu().numpy(), N, layout)
+    Lh = hp.from_device_order_host(LSE.cpu().numpy(), N, layout)
+    Ow, Lw = hp.oracle_forward(Q, K, V, sc)
+    tol_o, tol_l = TOL[dtype]
+    assert np.isfinite(Oh).all() and np.isfinite(Lh).all()
+    assert hp.max_abs_err(Oh, Ow) <= tol_o, (hp.max_abs_err(Oh, Ow), hp.layout_name(layout))
+    assert hp.max_abs_err(Lh, Lw) <= tol_l, (hp.max_abs_err(Lh, Lw), hp.layout_name(layout))
+
+
+@pytest.mark.parametrize("layout", [sa.CONTIGUOUS, sa.STRIPED])
+def test_tiny_fp32_config(layout):
+    # batch 1, 1 head, head_dim 64, seq 256, N = 4 (64-token shards), fp32, 4 x 4 steps
+    _check_ring(1, 1, 256, 64, 4, layout, torch.float32, seed=1)
+
+
+@pytest.mark.parametrize("layout", [sa.CONTIGUOUS, sa.STRIPED])
+@pytest.mark.parametrize("B,H,S,d,N,dtype", [
+    (2, 3, 120, 32, 4, torch.float32),     # ragged: c = 30, not a multiple of anything
+    (1, 2, 66, 8, 2, torch.float32),
+    (1, 1, 8, 4, 8, torch.float32),        # c = 1: striped steps with kv_dev > q_dev see nothing
+    (1, 2, 200, 128, 1, torch.float32),    # N = 1: plain causal attention
+    (1, 2, 256, 256, 4, torch.float32),    # largest head dimension
+    (2, 2, 192, 64, 4, torch.bfloat16),    # bf16 storage on the generic path
+    (1, 2, 96, 128, 4, torch.bfloat16),    # d = 128 but c = 24: not MFMA-eligible
+])
+def test_generic_shapes(layout, B, H, S, d, N, dtype):
+    _check_ring(B, H, S, d, N, layout, dtype, seed=S + d)
+
+
+@pytest.mark.parametrize("layout", [sa.CONTIGUOUS, sa.STRIPED])
+def test_driver_and_step_order(layout):
+    _check_ring(1, 2, 128, 64, 4, layout, torch.float32, seed=9, use_driver=True)
+    pairs = [(j, k) for j in range(4) for k in range(4)]
+    np.random.default_rng(1).shuffle(pairs)
+    _check_ring(1, 2, 128, 64, 4, layout, torch.float32, seed=9, order=pairs)
+
+
+@pytest.mark.parametrize("layout", [sa.CONTIGUOUS, sa.STRIPED])
+def test_single_steps_match_the_ring_oracle(layout):
+    # each (j, k) step on its own against the oracle's step with the mask taken
+    # from original token positions, starting from a non-trivial running state
+    B, H, S, d, N = 1, 1, 96, 32, 4
+    c = S // N
+    Q, K, V = inputs.qkv(B, H, S, d, 21, torch.float32)
+    Qn, Kn, Vn = (inputs.to_f64(x)[0, 0] for x in (Q, K, V))
+    scale = 0.3
+    for j in range(N):
+        for k in range(N):
+            qs, ks = slice(j * c, (j + 1) * c), slice(k * c, (k + 1) * c)
+            prev = (k + 1) % N                       # some other block as the earlier state
+            O0, L0 = orc.ring_step_fwd(np.zeros((c, d)), np.full(c, -np.inf), Qn[qs],
+                                       Kn[prev * c:(prev + 1) * c], Vn[prev * c:(prev + 1) * c],
+                                       j, prev, N, layout, scale)
+            Ow, Lw = orc.ring_step_fwd(O0, L0, Qn[qs], Kn[ks], Vn[ks], j, k, N, layout, scale)
+            Og = torch.from_numpy(O0).float().cuda()[None, None].contiguous()
+            Lg = torch.from_numpy(L0).float().cuda()[None, None].contiguous()
+            Qg, Kg, Vg = Q.cuda(), K.cuda(), V.cuda()
+            shape = sa.shard_shape(Qg, c, None, scale)
+            shape.stat_stride_b = shape.stat_stride_h = c
+            oshape = sa.SaShape.from_buffer_copy(shape)
+            # q/k/v live in the [1,1,S,d] tensor, o/lse in their own [1,1,c,(d)] tensors
+            sa.sa_attn_step_fwd(Qg[:, :, qs], Kg[:, :, ks], Vg[:, :, ks], Og, Lg, j, k, N, layout,
+                                oshape)
+            torch.cuda.synchronize()
+            Lh = Lg.cpu().numpy()[0, 0]
+            both_inf = np.isneginf(Lh) & np.isneginf(Lw)
+            assert (np.isneginf(Lh) == np.isneginf(Lw)).all(), (j, k)
+            assert hp.max_abs_err(Og.cpu().numpy()[0, 0], Ow) <= 1e-5, (j, k)
+            if not both_inf.all():
+                assert hp.max_abs_err(Lh[~both_inf], Lw[~both_inf]) <= 1e-5, (j, k)
+
+
+def test_finalize_rounds_to_storage_dtype():
+    x = inputs.gaussian((2, 2, 64, 128), 5).cuda()
+    shape = sa.shard_shape(x.to(torch.bfloat16), 64)
+    out = torch.empty_like(x, dtype=torch.bfloat16)
+    sa.sa_finalize(x, out, shape)
+    assert torch.equal(out, x.to(torch.bfloat16))
+    shape32 = sa.shard_shape(x, 64)
+    out32 = torch.empty_like(x)
+    sa.sa_finalize(x, out32, shape32)
+    assert torch.equal(out32, x)
