@@ -1,0 +1,237 @@
+#!/usr/bin/env python3
+"""Benchmark of the Striped Attention ring step on one MI355X.
+
+One bench "step" is one pass of the whole hot path for one device's share of the
+ring under the STRIPED layout: stripe-permute Q/K/V, initialise (O, LSE), play
+the device's N ring steps (forward; and backward when --bwd is on), and round
+the result to bf16.  `value` is the useful causal TFLOP/s of that pass (only
+unmasked query/key pairs count: 4*d flops each forward, 10*d backward) with
+inputs resident in HBM.  The contiguous (Ring Attention) layout is timed beside
+it for the worst-device step latencies the paper's argument is about (Sec. 1:
+a round lasts as long as its slowest device).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3|cfg2|cfg4|cfg5|tiny]
+
+Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2311_09431_amd import binding as sa   # noqa: E402
+from paper_2311_09431_amd import inputs           # noqa: E402
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+# one device's share: the worst-loaded query device of both layouts is N-1
+WORKLOADS = {
+    "cfg3": dict(B=1, H=32, d=128, S=262144, N=8, q_dev=7,
+                 desc="one device's share at 256k: B1 H32 d128 S262144 N8 (32768-token shards), "
+                      "bf16, all 8 steps of q_dev 7"),
+    "cfg2": dict(B=1, H=16, d=128, S=32768, N=8, q_dev=-1,
+                 desc="forward ring sim: B1 H16 d128 S32768 N8 (4096-token shards), bf16, all 64 steps"),
+    "cfg4": dict(B=1, H=16, d=128, S=131072, N=8, q_dev=7,
+                 desc="B1 H16 d128 S131072 N8 (16384-token shards), bf16, q_dev 7"),
+    "cfg5": dict(B=1, H=8, d=128, S=786432, N=16, q_dev=15,
+                 desc="one device's share at 786k: B1 H8 d128 S786432 N16 (49152-token shards), bf16, "
+                      "q_dev 15"),
+    "tiny": dict(B=1, H=2, d=128, S=4096, N=4, q_dev=-1, desc="B1 H2 d128 S4096 N4, bf16 (quick check)"),
+}
+
+
+def step_pairs(w, layout, j, k):
+    return sa.sa_step_pairs(j, k, w["N"], layout, w["S"] // w["N"])
+
+
+def played_steps(w):
+    N = w["N"]
+    devs = range(N) if w["q_dev"] < 0 else [w["q_dev"]]
+    return [(i, j, (j - i) % N) for i in range(N) for j in devs]
+
+
+def useful_flops(w, layout, per_pair):
+    return sum(step_pairs(w, layout, j, k) for _, j, k in played_steps(w)) * w["B"] * w["H"] * per_pair * w["d"]
+
+
+class Runner:
+    def __init__(self, w, seed, bwd):
+        self.w, self.bwd = w, bwd
+        B, H, S, d, N = w["B"], w["H"], w["S"], w["d"], w["N"]
+        dev = "cuda"
+        n_in = 4 if bwd else 3
+        self.orig = [inputs.gaussian((B, H, S, d), seed * 16 + i, torch.bfloat16, device=dev)
+                     for i in range(n_in)]
+        self.perm = [torch.empty_like(x) for x in self.orig]
+        self.O = torch.empty(B, H, S, d, dtype=torch.float32, device=dev)
+        self.LSE = torch.empty(B, H, S, dtype=torch.float32, device=dev)
+        self.out = torch.empty(B, H, S, d, dtype=torch.bfloat16, device=dev)
+        self.c = S // N
+        self.shape = sa.shard_shape(self.orig[0], self.c, self.LSE)
+        if bwd:
+            self.delta = torch.empty_like(self.LSE)
+            self.dQ, self.dK, self.dV = (torch.empty_like(self.O) for _ in range(3))
+
+    def one_pass(self, layout, timed):
+        """The hot path for the played device(s).  Returns per-step ms tables or None."""
+        w, c = self.w, self.c
+        if layout == sa.STRIPED:
+            for x, y in zip(self.orig, self.perm):
+                sa.sa_stripe_permute(x, y, w["N"])
+            ins = self.perm
+        else:
+            ins = self.orig
+        t_f = sa.sa_ring_fwd(ins[0], ins[1], ins[2], self.O, self.LSE, w["N"], layout, self.shape,
+                             w["q_dev"], timed)
+        devs = range(w["N"]) if w["q_dev"] < 0 else [w["q_dev"]]
+        for j in devs:
+            sa.sa_finalize(self.O[:, :, j * c:], self.out[:, :, j * c:], self.shape)
+        t_b = None
+        if self.bwd:
+            t_b = sa.sa_ring_bwd(ins[0], ins[1], ins[2], ins[3], self.O, self.LSE, self.delta, self.dQ,
+                                 self.dK, self.dV, w["N"], layout, self.shape, w["q_dev"], timed)
+        return t_f, t_b
+
+
+def summarize_steps(w, layout, table, per_pair):
+    """Per-step latency / TFLOP/s rows and the worst-device latency of every round."""
+    N = w["N"]
+    rows, worst = [], []
+    for i in range(N):
+        ms_round = 0.0
+        for _, j, k in [s for s in played_steps(w) if s[0] == i]:
+            ms = table[i][j]
+            pairs = step_pairs(w, layout, j, k)
+            fl = pairs * w["B"] * w["H"] * per_pair * w["d"]
+            rows.append(dict(round=i, q_dev=j, kv_dev=k, ms=round(ms, 4),
+                             tflops=round(fl / (ms * 1e9), 1) if ms > 0 else 0.0))
+            ms_round = max(ms_round, ms)
+        worst.append(round(ms_round, 4))
+    return rows, worst
+
+
+def cpu_baseline(seconds_budget=20.0):
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload
+    shape: one head of d = 128 at a sequence length it finishes in ~10-30 s."""
+    import numpy as np
+    from oracle import striped_attention as orc
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = 1
+    S, d = 49152, 128
+    q, k, v = (inputs.to_f64(x)[0, 0] for x in inputs.qkv(1, 1, S, d, 99, torch.bfloat16))
+    t0 = time.perf_counter()
+    orc.causal_attention(q, k, v, 1.0 / np.sqrt(d))
+    dt = time.perf_counter() - t0
+    flops = S * (S + 1) // 2 * 4 * d
+    return dict(value=flops / dt / 1e12, unit="TFLOP/s (useful causal, fp64)", cores=cores,
+                kind="oracle", seconds=round(dt, 2),
+                sample="oracle.causal_attention on 1 head, d=128, S=%d (%.1f GFLOP useful), forward" %
+                       (S, flops / 1e9))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="cfg3", choices=sorted(WORKLOADS))
+    ap.add_argument("--bwd", type=int, default=0, help="1: include the backward ring in the pass")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=3)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (the ring's N devices are played in sequence on "
+              "it); --gpus N > 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    sa.lib()
+    w = WORKLOADS[args.workload]
+    run = Runner(w, args.seed, bool(args.bwd))
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        run.one_pass(sa.STRIPED, False)
+    torch.cuda.synchronize()
+    # timed region: K passes of the striped hot path, per-step HIP events inside
+    tables_f, tables_b = [], []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        tf, tb = run.one_pass(sa.STRIPED, True)
+        tables_f.append(tf)
+        tables_b.append(tb)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    N = w["N"]
+    avg = lambda tabs: [[sum(t[i][j] for t in tabs) / len(tabs) for j in range(N)] for i in range(N)]
+    per_pair_total = 4 + (10 if args.bwd else 0)
+    flops = useful_flops(w, sa.STRIPED, per_pair_total)
+    value = flops / (ms_per_step * 1e9)
+    striped_rows, striped_worst = summarize_steps(w, sa.STRIPED, avg(tables_f), 4)
+
+    # the comparison layout, same shapes (not part of `value`)
+    run.one_pass(sa.CONTIGUOUS, False)
+    torch.cuda.synchronize()
+    ctab_f, ctab_b = [], []
+    for _ in range(max(1, args.steps)):
+        tf, tb = run.one_pass(sa.CONTIGUOUS, True)
+        ctab_f.append(tf)
+        ctab_b.append(tb)
+    contig_rows, contig_worst = summarize_steps(w, sa.CONTIGUOUS, avg(ctab_f), 4)
+
+    # roofline of the dominant kernel (the forward MFMA step; the backward step when on):
+    # algorithmic flops of one launch / its average HIP-event duration
+    if args.bwd:
+        rows_dom, _ = summarize_steps(w, sa.STRIPED, avg(tables_b), 10)
+        dom_name = "bwd ring step"
+    else:
+        rows_dom, dom_name = striped_rows, "fwd ring step"
+    live = [r for r in rows_dom if r["ms"] > 0]
+    ach = sum(r["tflops"] * r["ms"] for r in live) / max(1e-9, sum(r["ms"] for r in live))
+    roofline = dict(bound="mfma", kernel=dom_name, achieved=round(ach, 1), peak=PEAK_BF16_TFLOPS,
+                    unit="TFLOP/s", frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=None,
+                    avg_launch_ms=round(sum(r["ms"] for r in live) / max(1, len(live)), 4))
+
+    result = {
+        "metric": "useful causal TFLOP/s per ring step (striped layout, worst-loaded device's share)",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload + ": " + w["desc"], "B": w["B"], "H": w["H"], "d": w["d"],
+                   "n_seq": w["S"], "N": N, "c": w["S"] // N, "q_dev": w["q_dev"],
+                   "pass": "stripe_permute + ring fwd" + (" + ring bwd" if args.bwd else "") + " + finalize"},
+        "frac_of_bf16_peak": round(value / PEAK_BF16_TFLOPS, 4),
+        "roofline": roofline,
+        "striped": {"worst_device_ms_per_round": striped_worst, "ring_sum_ms": round(sum(striped_worst), 4),
+                    "steps": striped_rows},
+        "contiguous": {"worst_device_ms_per_round": contig_worst, "ring_sum_ms": round(sum(contig_worst), 4),
+                       "steps": contig_rows},
+        "worst_device_latency_ratio_contiguous_over_striped":
+            round(sum(contig_worst) / max(1e-9, sum(striped_worst)), 3),
+        "paper_context": "end-to-end training speedups 1.45x (256k, 8xA100) and 1.65x (786k, 16 TPUv4); "
+                         "not step latencies",
+    }
+    if args.bwd:
+        rb, wb = summarize_steps(w, sa.STRIPED, avg(tables_b), 10)
+        result["striped"]["bwd_steps"], result["striped"]["bwd_worst_device_ms_per_round"] = rb, wb
+        rb, wb = summarize_steps(w, sa.CONTIGUOUS, avg(ctab_b), 10)
+        result["contiguous"]["bwd_steps"], result["contiguous"]["bwd_worst_device_ms_per_round"] = rb, wb
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

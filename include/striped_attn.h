@@ -62,7 +62,8 @@ typedef struct {
  * permutation followed by a contiguous split).  src and dst are [outer, n_seq,
  * inner_bytes] byte arrays; dst[o, (t mod N) * c + t div N, :] = src[o, t, :]
  * with c = n_seq / N.  Serves Q/K/V rows as well as token ids, position ids and
- * targets.  Bit-exact byte movement.  src and dst must not overlap.
+ * targets.  Bit-exact byte movement.  src and dst must not overlap.  outer == 0
+ * or n_seq == 0 is a successful no-op (pointers are then not looked at).
  * Errors: NULL, n_seq % N != 0 or sizes <= 0 (SHAPE), N < 1 (DEV), src == dst
  * (LAYOUT), misalignment (ALIGN).
  */

@@ -56,9 +56,10 @@ StepArgs make_args(const sa_shape* s) {
 
 int permute_common(const void* src, void* dst, int64_t outer, int64_t n_seq, int64_t inner_bytes,
                    int N, bool inverse, void* stream) {
-    if (!src || !dst) return SA_ERR_NULL;
     if (N < 1) return SA_ERR_DEV;
     if (outer < 0 || n_seq < 0 || inner_bytes < 1 || n_seq % N) return SA_ERR_SHAPE;
+    if (outer == 0 || n_seq == 0) return SA_OK;   // empty: nothing to move, pointers may be NULL
+    if (!src || !dst) return SA_ERR_NULL;
     if (src == dst) return SA_ERR_LAYOUT;
     int64_t al = 16;
     while (inner_bytes % al) al >>= 1;

@@ -1,5 +1,239 @@
+// Forward ring step on the CDNA4 matrix cores (bf16 operands, fp32 accumulate),
+// head dimension 128: AccumulateAttentionFragment of Algorithm 1 with the fused
+// log-sum-exp merge, skipping every key tile that GetMask(j, k) masks entirely
+// (Sec. 2.2.1) at a 64-key granularity per 32-query wavefront.
+//
+// Work decomposition.  A workgroup of 4 wavefronts owns 128 query rows; each
+// wavefront owns 32 of them for the whole kernel.  Key/value tiles of 64 rows
+// stream through LDS, double buffered (one barrier per tile).
+//
+// Register layouts (v_mfma_f32_32x32x16_bf16: lane = 32*h + n):
+//   A operand: row n of the 32 x 16 left matrix, 8 consecutive k starting at 8h
+//   B operand: column n of the 16 x 32 right matrix, the same 8 k
+//   C/D:       column n, rows 8*(r/4) + 4h + r%4 for register r = 0..15
+// The scores are computed TRANSPOSED, S^T = K Q^T (A = key rows from LDS, B = the
+// query rows, resident in registers), so that a lane holds 16 + 16 keys of ONE
+// query: the row max / row sum of the online softmax are in-lane reductions
+// plus a single exchange between the two half-waves, and the probabilities
+// already sit in the B-operand layout of the second product O^T += V^T P^T
+// (A = V^T rows from LDS).  The contraction index of that product is the key;
+// a lane's 8 B-operand keys are {0..3, 8..11} + 4h of each group of 16, so V^T is
+// stored in LDS with the keys of every group of 16 in that order and one 16-byte
+// LDS read feeds one MFMA.
+//
+// Online softmax in base 2: kappa = scale * log2(e) is folded into the exponent,
+// p = exp2(s * kappa - m).  The running state enters as (acc = O, m = LSE *
+// log2(e), l = 1) and leaves as O = acc / l, LSE = (m + log2 l) * ln 2, which is
+// the log-sum-exp merge of the step's partial result with the running one.
+// Row sums are taken over the fp32 probabilities before they are rounded to
+// bf16 for the second product.
+#include <hip/hip_bf16.h>
+
 #include "sa_internal.h"
+
 namespace sa {
-bool fwd_mfma_supported(const StepArgs&, int) { return false; }
-hipError_t launch_fwd_mfma(const StepArgs&, hipStream_t) { return hipErrorNotSupported; }
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int BM = 128;        // query rows per workgroup
+constexpr int BN = 64;         // key rows per tile
+constexpr int D = 128;         // head dimension
+constexpr int KS = D + 8;      // LDS row stride of the K tile, elements (272 B: conflict-free b128 reads)
+constexpr int VS = BN + 8;     // LDS row stride of the V^T tile, elements (144 B)
+constexpr int K_TILE = BN * KS;
+constexpr int V_TILE = D * VS;
+constexpr int BUF = K_TILE + V_TILE;          // elements per pipeline stage
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+
+
+// Global -> registers for key tile kt.  K: thread t takes 16-byte chunk t%16 of
+// rows t/16 + 16 i.  V: thread t takes the d-pair t%64 of the key quads
+// (t/64) + 4 i, one 4-byte load per key, so a wavefront reads whole 256-byte rows.
+// rk: 4 x 16 B of the K tile; rv: 4 key quads x 4 keys x one d-pair of the V tile.
+__device__ inline void load_tile(uint4 (&rk)[4], uint32_t (&rv)[16], const __bf16* __restrict__ K,
+                                 const __bf16* __restrict__ V, int kt, int tid) {
+    const __bf16* kp = K + (int64_t)(kt * BN + (tid >> 4)) * D + (tid & 15) * 8;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) rk[i] = *reinterpret_cast<const uint4*>(kp + (int64_t)i * 16 * D);
+    const __bf16* vp = V + (int64_t)(kt * BN + 4 * (tid >> 6)) * D + (tid & 63) * 2;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            rv[4 * i + j] = *reinterpret_cast<const uint32_t*>(vp + (int64_t)(16 * i + j) * D);
+}
+
+// Registers -> LDS stage.  K row-major; V transposed ([d][key]) with the key
+// quads of each group of 16 stored in the order 0, 2, 1, 3.
+__device__ inline void store_tile(const uint4 (&rk)[4], const uint32_t (&rv)[16],
+                                  __bf16* __restrict__ stage, int tid) {
+    __bf16* kl = stage + (tid >> 4) * KS + (tid & 15) * 8;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4*>(kl + i * 16 * KS) = rk[i];
+    __bf16* vl = stage + K_TILE + (tid & 63) * 2 * VS;
+    const int q = tid >> 6;                       // quad index within a group of 16 keys
+    const int pos = 4 * (((q & 1) << 1) | (q >> 1));
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {                 // group of 16 keys
+        uint2 lo, hi;
+        lo.x = __builtin_amdgcn_perm(rv[4 * i + 1], rv[4 * i + 0], 0x05040100u);
+        lo.y = __builtin_amdgcn_perm(rv[4 * i + 3], rv[4 * i + 2], 0x05040100u);
+        hi.x = __builtin_amdgcn_perm(rv[4 * i + 1], rv[4 * i + 0], 0x07060302u);
+        hi.y = __builtin_amdgcn_perm(rv[4 * i + 3], rv[4 * i + 2], 0x07060302u);
+        *reinterpret_cast<uint2*>(vl + 16 * i + pos) = lo;
+        *reinterpret_cast<uint2*>(vl + VS + 16 * i + pos) = hi;
+    }
+}
+
+__global__ void __launch_bounds__(256, 2)
+fwd_mfma_kernel(StepArgs p, int n_qtiles) {
+    __shared__ __attribute__((aligned(16))) __bf16 lds[2 * BUF];
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, h = lane >> 5;
+    const bool tri = p.kind == MASK_TRI;
+    // triangular steps: heaviest query tiles first
+    const int qt = tri ? n_qtiles - 1 - (int)blockIdx.x : (int)blockIdx.x;
+    const int bh = blockIdx.y, b = bh / p.H, hd = bh - b * p.H;
+    const int64_t base = b * p.stride_b + hd * p.stride_h;
+    const __bf16* Q = (const __bf16*)p.q + base;
+    const __bf16* K = (const __bf16*)p.k + base;
+    const __bf16* V = (const __bf16*)p.v + base;
+    float* O = p.o + base;
+    float* L = p.lse + b * p.stat_stride_b + hd * p.stat_stride_h;
+
+    const int q0 = qt * BM;
+    const int a_lo = q0 + 32 * wave;          // first query row of this wavefront
+    const int a = a_lo + n;                   // this lane's query row
+    const int off = p.off;
+    // key tiles holding at least one allowed pair: for the workgroup / for this wavefront
+    const int n_kt = tri ? min(p.c / BN, (q0 + BM - 1 - off) / BN + 1) : p.c / BN;
+    const int wave_last = tri ? (a_lo + 31 - off) / BN : n_kt - 1;
+
+    // query rows as B operands: 8 k-steps of 16
+    bf16x8 qf[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+        qf[ks] = *reinterpret_cast<const bf16x8*>(Q + (int64_t)a * D + 16 * ks + 8 * h);
+
+    // running state -> accumulators
+    const float kappa = p.scale * LOG2E;
+    float m = L[a] * LOG2E;                   // -inf stays -inf
+    float l = (h == 0) ? 1.f : 0.f;           // the two half-waves hold partial row sums
+    f32x16 oacc[4];
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const float4 x = *reinterpret_cast<const float4*>(O + (int64_t)a * D + 32 * mb + 8 * g + 4 * h);
+            oacc[mb][4 * g + 0] = x.x; oacc[mb][4 * g + 1] = x.y;
+            oacc[mb][4 * g + 2] = x.z; oacc[mb][4 * g + 3] = x.w;
+        }
+
+    uint4 rk[4];
+    uint32_t rv[16];
+    load_tile(rk, rv, K, V, 0, tid);
+    store_tile(rk, rv, lds, tid);
+    __syncthreads();
+
+    for (int kt = 0; kt < n_kt; ++kt) {
+        const __bf16* stage = lds + (kt & 1) * BUF;
+        // prefetch the next tile into registers (the last iteration re-reads its own
+        // tile into the idle stage, which keeps the loop free of branches)
+        load_tile(rk, rv, K, V, min(kt + 1, n_kt - 1), tid);
+
+        if (kt <= wave_last) {
+            // S^T = K Q^T : two blocks of 32 keys x 32 queries
+            f32x16 s[2];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
+                const __bf16* kl = stage + (kb * 32 + n) * KS + 8 * h;
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks) {
+                    const bf16x8 ka = *reinterpret_cast<const bf16x8*>(kl + 16 * ks);
+                    s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[ks], s[kb], 0, 0, 0);
+                }
+            }
+            // element mask, only on tiles crossing the diagonal: allowed iff key <= a - off
+            if (tri && kt * BN + BN - 1 > a_lo - off) {
+                const int lim = a - off - kt * BN - 4 * h;   // allowed iff 8*(r/4) + r%4 + 32 kb <= lim
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (32 * kb + 8 * (r / 4) + (r % 4) > lim) s[kb][r] = -INFINITY;
+            }
+            // online softmax, base 2
+            float mx = s[0][0];
+#pragma unroll
+            for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[0][r]);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[1][r]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(m, mx * kappa);
+            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;   // row with no key so far
+            const float alpha = __builtin_amdgcn_exp2f(m - m_use);
+            m = m_new;
+            float rs = 0.f;
+            bf16x8 pb[4];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float pr = __builtin_amdgcn_exp2f(fmaf(s[kb][r], kappa, -m_use));
+                    rs += pr;
+                    pb[2 * kb + r / 8][r % 8] = (__bf16)pr;
+                }
+            l = l * alpha + rs;
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[mb][r] *= alpha;
+            // O^T += V^T P^T : 4 blocks of 32 d-rows, 4 k-steps of 16 keys
+            const __bf16* vl = stage + K_TILE + n * VS + 8 * h;
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+#pragma unroll
+                for (int mb = 0; mb < 4; ++mb) {
+                    const bf16x8 va = *reinterpret_cast<const bf16x8*>(vl + 32 * mb * VS + 16 * g);
+                    oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[g], oacc[mb], 0, 0, 0);
+                }
+        }
+
+        store_tile(rk, rv, lds + ((kt + 1) & 1) * BUF, tid);
+        __syncthreads();
+    }
+
+    // epilogue: normalise, store the merged state
+    const float l_tot = l + __shfl_xor(l, 32);
+    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            float4 x;
+            x.x = oacc[mb][4 * g + 0] * inv; x.y = oacc[mb][4 * g + 1] * inv;
+            x.z = oacc[mb][4 * g + 2] * inv; x.w = oacc[mb][4 * g + 3] * inv;
+            *reinterpret_cast<float4*>(O + (int64_t)a * D + 32 * mb + 8 * g + 4 * h) = x;
+        }
+    if (h == 0) L[a] = (m + __builtin_amdgcn_logf(l_tot)) * LN2;
+}
+
+}  // namespace
+
+bool fwd_mfma_supported(const StepArgs& a, int dtype) {
+    return dtype == SA_BF16 && a.d == D && a.c % BM == 0;
+}
+
+hipError_t launch_fwd_mfma(const StepArgs& a, hipStream_t st) {
+    const int n_qtiles = a.c / BM;
+    hipLaunchKernelGGL(fwd_mfma_kernel, dim3(n_qtiles, a.B * a.H), dim3(256), 0, st, a, n_qtiles);
+    return hipGetLastError();
+}
+
 }  // namespace sa

@@ -103,3 +103,29 @@ def test_finalize_rounds_to_storage_dtype():
     out32 = torch.empty_like(x)
     sa.sa_finalize(x, out32, shape32)
     assert torch.equal(out32, x)
+
+
+@pytest.mark.parametrize("layout", [sa.CONTIGUOUS, sa.STRIPED])
+@pytest.mark.parametrize("B,H,S,N", [
+    (1, 2, 512, 4),      # c = 128: one query tile, two key tiles per step
+    (2, 2, 1024, 4),     # c = 256
+    (1, 3, 2048, 2),     # c = 1024: 8 query tiles, several unmasked tiles before the diagonal
+    (1, 1, 1152, 3),     # c = 384: odd number of query tiles
+    (1, 2, 1024, 1),     # N = 1
+])
+def test_mfma_bf16_ring(layout, B, H, S, N):
+    # bf16, d = 128, c % 128 == 0: the matrix-core kernel
+    _check_ring(B, H, S, 128, N, layout, torch.bfloat16, seed=S + N, use_driver=(N == 4))
+
+
+@pytest.mark.parametrize("layout", [sa.CONTIGUOUS, sa.STRIPED])
+def test_mfma_bf16_scale_and_order(layout):
+    pairs = [(j, k) for j in range(4) for k in range(4)]
+    np.random.default_rng(2).shuffle(pairs)
+    _check_ring(1, 2, 1024, 128, 4, layout, torch.bfloat16, seed=77, scale=0.05, order=pairs)
+
+
+def test_mfma_matches_generic_kernel_on_large_scores():
+    # unit-variance q.k with scale 1 gives scores of magnitude ~ sqrt(128): a hard
+    # softmax, checked against the oracle with the same tolerances
+    _check_ring(1, 1, 512, 128, 2, sa.STRIPED, torch.bfloat16, seed=5, scale=1.0)
