@@ -29,64 +29,29 @@
 // bf16 for the second product.
 #include <hip/hip_bf16.h>
 
+#include "mfma_tiles.h"
 #include "sa_internal.h"
 
 namespace sa {
 
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-
 constexpr int BM = 128;        // query rows per workgroup
-constexpr int BN = 64;         // key rows per tile
-constexpr int D = 128;         // head dimension
-constexpr int KS = D + 8;      // LDS row stride of the K tile, elements (272 B: conflict-free b128 reads)
-constexpr int VS = BN + 8;     // LDS row stride of the V^T tile, elements (144 B)
-constexpr int K_TILE = BN * KS;
-constexpr int V_TILE = D * VS;
-constexpr int BUF = K_TILE + V_TILE;          // elements per pipeline stage
-constexpr float LOG2E = 1.4426950408889634f;
-constexpr float LN2 = 0.6931471805599453f;
+constexpr int BN = TR;         // key rows per tile
+constexpr int D = TD;          // head dimension
+constexpr int K_TILE = ROW_TILE;
+constexpr int BUF = ROW_TILE + TRN_TILE;      // elements per pipeline stage: K rows, V^T
 
-
-// Global -> registers for key tile kt.  K: thread t takes 16-byte chunk t%16 of
-// rows t/16 + 16 i.  V: thread t takes the d-pair t%64 of the key quads
-// (t/64) + 4 i, one 4-byte load per key, so a wavefront reads whole 256-byte rows.
-// rk: 4 x 16 B of the K tile; rv: 4 key quads x 4 keys x one d-pair of the V tile.
-__device__ inline void load_tile(uint4 (&rk)[4], uint32_t (&rv)[16], const __bf16* __restrict__ K,
+// Global -> registers and registers -> LDS stage for key tile kt.
+__device__ inline void load_tile(u32x4 (&rk)[4], uint32_t (&rv)[16], const __bf16* __restrict__ K,
                                  const __bf16* __restrict__ V, int kt, int tid) {
-    const __bf16* kp = K + (int64_t)(kt * BN + (tid >> 4)) * D + (tid & 15) * 8;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) rk[i] = *reinterpret_cast<const uint4*>(kp + (int64_t)i * 16 * D);
-    const __bf16* vp = V + (int64_t)(kt * BN + 4 * (tid >> 6)) * D + (tid & 63) * 2;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            rv[4 * i + j] = *reinterpret_cast<const uint32_t*>(vp + (int64_t)(16 * i + j) * D);
+    load_rows(rk, K + (int64_t)kt * BN * D, tid);
+    load_quads(rv, V + (int64_t)kt * BN * D, tid);
 }
-
-// Registers -> LDS stage.  K row-major; V transposed ([d][key]) with the key
-// quads of each group of 16 stored in the order 0, 2, 1, 3.
-__device__ inline void store_tile(const uint4 (&rk)[4], const uint32_t (&rv)[16],
+__device__ inline void store_tile(const u32x4 (&rk)[4], const uint32_t (&rv)[16],
                                   __bf16* __restrict__ stage, int tid) {
-    __bf16* kl = stage + (tid >> 4) * KS + (tid & 15) * 8;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4*>(kl + i * 16 * KS) = rk[i];
-    __bf16* vl = stage + K_TILE + (tid & 63) * 2 * VS;
-    const int q = tid >> 6;                       // quad index within a group of 16 keys
-    const int pos = 4 * (((q & 1) << 1) | (q >> 1));
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {                 // group of 16 keys
-        uint2 lo, hi;
-        lo.x = __builtin_amdgcn_perm(rv[4 * i + 1], rv[4 * i + 0], 0x05040100u);
-        lo.y = __builtin_amdgcn_perm(rv[4 * i + 3], rv[4 * i + 2], 0x05040100u);
-        hi.x = __builtin_amdgcn_perm(rv[4 * i + 1], rv[4 * i + 0], 0x07060302u);
-        hi.y = __builtin_amdgcn_perm(rv[4 * i + 3], rv[4 * i + 2], 0x07060302u);
-        *reinterpret_cast<uint2*>(vl + 16 * i + pos) = lo;
-        *reinterpret_cast<uint2*>(vl + VS + 16 * i + pos) = hi;
-    }
+    store_rows(rk, stage, tid);
+    store_transposed(rv, stage + K_TILE, tid);
 }
 
 __global__ void __launch_bounds__(256, 2)
@@ -115,9 +80,7 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
 
     // query rows as B operands: 8 k-steps of 16
     bf16x8 qf[8];
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks)
-        qf[ks] = *reinterpret_cast<const bf16x8*>(Q + (int64_t)a * D + 16 * ks + 8 * h);
+    load_b_frags(qf, Q + (int64_t)a * D, h);
 
     // running state -> accumulators
     const float kappa = p.scale * LOG2E;
@@ -133,7 +96,7 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
             oacc[mb][4 * g + 2] = x.z; oacc[mb][4 * g + 3] = x.w;
         }
 
-    uint4 rk[4];
+    u32x4 rk[4];
     uint32_t rv[16];
     load_tile(rk, rv, K, V, 0, tid);
     store_tile(rk, rv, lds, tid);
@@ -152,12 +115,9 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
             for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
-                const __bf16* kl = stage + (kb * 32 + n) * KS + 8 * h;
 #pragma unroll
-                for (int ks = 0; ks < 8; ++ks) {
-                    const bf16x8 ka = *reinterpret_cast<const bf16x8*>(kl + 16 * ks);
-                    s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[ks], s[kb], 0, 0, 0);
-                }
+                for (int ks = 0; ks < 8; ++ks)
+                    s[kb] = mfma(read_a_rows(stage, kb * 32 + n, ks, h), qf[ks], s[kb]);
             }
             // element mask, only on tiles crossing the diagonal: allowed iff key <= a - off
             if (tri && kt * BN + BN - 1 > a_lo - off) {
@@ -195,14 +155,11 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) oacc[mb][r] *= alpha;
             // O^T += V^T P^T : 4 blocks of 32 d-rows, 4 k-steps of 16 keys
-            const __bf16* vl = stage + K_TILE + n * VS + 8 * h;
 #pragma unroll
             for (int g = 0; g < 4; ++g)
 #pragma unroll
-                for (int mb = 0; mb < 4; ++mb) {
-                    const bf16x8 va = *reinterpret_cast<const bf16x8*>(vl + 32 * mb * VS + 16 * g);
-                    oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[g], oacc[mb], 0, 0, 0);
-                }
+                for (int mb = 0; mb < 4; ++mb)
+                    oacc[mb] = mfma(read_a_trn(stage + K_TILE, 32 * mb + n, g, h), pb[g], oacc[mb]);
         }
 
         store_tile(rk, rv, lds + ((kt + 1) & 1) * BUF, tid);

@@ -55,3 +55,14 @@ def test_bwd_preprocess_matches_rowsum():
     sa.sa_bwd_preprocess(o, g, delta, sa.shard_shape(g, 100, delta))
     want = (inputs.to_f64(o) * inputs.to_f64(g)).sum(-1)
     assert hp.max_abs_err(delta.cpu().numpy(), want) <= 1e-4
+
+
+@pytest.mark.parametrize("layout", [sa.CONTIGUOUS, sa.STRIPED])
+@pytest.mark.parametrize("B,H,S,N", [
+    (1, 2, 512, 4),      # c = 128
+    (2, 1, 1024, 2),     # c = 512: tiles before, on and after the diagonal
+    (1, 1, 1152, 3),     # c = 384
+    (1, 2, 768, 1),      # N = 1
+])
+def test_mfma_bf16_backward(layout, B, H, S, N):
+    _check(B, H, S, 128, N, layout, torch.bfloat16, seed=S + N + 5, use_driver=(N != 2))
