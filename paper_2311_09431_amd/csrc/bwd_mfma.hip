@@ -49,8 +49,10 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, h = lane >> 5;
     const bool tri = p.kind == MASK_TRI;
-    const int qt = tri ? n_tiles - 1 - (int)blockIdx.x : (int)blockIdx.x;   // heaviest first
-    const int bh = blockIdx.y, b = bh / p.H, hd = bh - b * p.H;
+    int rank, bh;
+    decode_block((int)blockIdx.x, n_tiles, p.B * p.H, rank, bh);
+    const int qt = tri ? n_tiles - 1 - rank : rank;      // heaviest query tiles first
+    const int b = bh / p.H, hd = bh - b * p.H;
     const int64_t base = b * p.stride_b + hd * p.stride_h;
     const int64_t sbase = b * p.stat_stride_b + hd * p.stat_stride_h;
     const __bf16* Q = (const __bf16*)p.q + base;
@@ -152,8 +154,9 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, h = lane >> 5;
     const bool tri = p.kind == MASK_TRI;
-    const int ktile = (int)blockIdx.x;            // triangular steps: low key tiles see most queries: first
-    const int bh = blockIdx.y, b = bh / p.H, hd = bh - b * p.H;
+    int ktile, bh;                                // triangular steps: low key tiles see most queries: first
+    decode_block((int)blockIdx.x, n_tiles, p.B * p.H, ktile, bh);
+    const int b = bh / p.H, hd = bh - b * p.H;
     const int64_t base = b * p.stride_b + hd * p.stride_h;
     const int64_t sbase = b * p.stat_stride_b + hd * p.stat_stride_h;
     const __bf16* Q = (const __bf16*)p.q + base;
@@ -277,10 +280,10 @@ bool bwd_mfma_supported(const StepArgs& a, int dtype) {
 
 hipError_t launch_bwd_mfma(const StepArgs& a, hipStream_t st) {
     const int n_tiles = a.c / BM;
-    hipLaunchKernelGGL(bwd_dq_mfma_kernel, dim3(n_tiles, a.B * a.H), dim3(256), 0, st, a, n_tiles);
+    hipLaunchKernelGGL(bwd_dq_mfma_kernel, dim3(n_tiles * a.B * a.H), dim3(256), 0, st, a, n_tiles);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(bwd_dkdv_mfma_kernel, dim3(n_tiles, a.B * a.H), dim3(256), 0, st, a, n_tiles);
+    hipLaunchKernelGGL(bwd_dkdv_mfma_kernel, dim3(n_tiles * a.B * a.H), dim3(256), 0, st, a, n_tiles);
     return hipGetLastError();
 }
 

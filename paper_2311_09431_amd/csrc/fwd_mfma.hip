@@ -7,19 +7,13 @@
 // wavefront owns 32 of them for the whole kernel.  Key/value tiles of 64 rows
 // stream through LDS, double buffered (one barrier per tile).
 //
-// Register layouts (v_mfma_f32_32x32x16_bf16: lane = 32*h + n):
-//   A operand: row n of the 32 x 16 left matrix, 8 consecutive k starting at 8h
-//   B operand: column n of the 16 x 32 right matrix, the same 8 k
-//   C/D:       column n, rows 8*(r/4) + 4h + r%4 for register r = 0..15
 // The scores are computed TRANSPOSED, S^T = K Q^T (A = key rows from LDS, B = the
 // query rows, resident in registers), so that a lane holds 16 + 16 keys of ONE
 // query: the row max / row sum of the online softmax are in-lane reductions
 // plus a single exchange between the two half-waves, and the probabilities
-// already sit in the B-operand layout of the second product O^T += V^T P^T
-// (A = V^T rows from LDS).  The contraction index of that product is the key;
-// a lane's 8 B-operand keys are {0..3, 8..11} + 4h of each group of 16, so V^T is
-// stored in LDS with the keys of every group of 16 in that order and one 16-byte
-// LDS read feeds one MFMA.
+// already sit in the B-operand layout of the second product O^T += V^T P^T.
+// Its A operand, V^T, is read from the row-major V tile with the transposing
+// LDS read, so both tiles are staged with plain 16-byte copies.
 //
 // Online softmax in base 2: kappa = scale * log2(e) is folded into the exponent,
 // p = exp2(s * kappa - m).  The running state enters as (acc = O, m = LSE *
@@ -40,18 +34,18 @@ constexpr int BM = 128;        // query rows per workgroup
 constexpr int BN = TR;         // key rows per tile
 constexpr int D = TD;          // head dimension
 constexpr int K_TILE = ROW_TILE;
-constexpr int BUF = ROW_TILE + TRN_TILE;      // elements per pipeline stage: K rows, V^T
+constexpr int BUF = ROW_TILE + X_TILE;        // elements per pipeline stage: K rows, V rows
 
 // Global -> registers and registers -> LDS stage for key tile kt.
-__device__ inline void load_tile(u32x4 (&rk)[4], uint32_t (&rv)[16], const __bf16* __restrict__ K,
+__device__ inline void load_tile(u32x4 (&rk)[4], u32x4 (&rv)[4], const __bf16* __restrict__ K,
                                  const __bf16* __restrict__ V, int kt, int tid) {
     load_rows(rk, K + (int64_t)kt * BN * D, tid);
-    load_quads(rv, V + (int64_t)kt * BN * D, tid);
+    load_rows(rv, V + (int64_t)kt * BN * D, tid);
 }
-__device__ inline void store_tile(const u32x4 (&rk)[4], const uint32_t (&rv)[16],
+__device__ inline void store_tile(const u32x4 (&rk)[4], const u32x4 (&rv)[4],
                                   __bf16* __restrict__ stage, int tid) {
     store_rows(rk, stage, tid);
-    store_transposed(rv, stage + K_TILE, tid);
+    store_rows_x(rv, stage + K_TILE, tid);
 }
 
 __global__ void __launch_bounds__(256, 2)
@@ -60,9 +54,10 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, h = lane >> 5;
     const bool tri = p.kind == MASK_TRI;
-    // triangular steps: heaviest query tiles first
-    const int qt = tri ? n_qtiles - 1 - (int)blockIdx.x : (int)blockIdx.x;
-    const int bh = blockIdx.y, b = bh / p.H, hd = bh - b * p.H;
+    int rank, bh;
+    decode_block((int)blockIdx.x, n_qtiles, p.B * p.H, rank, bh);
+    const int qt = tri ? n_qtiles - 1 - rank : rank;      // triangular steps: heaviest query tiles first
+    const int b = bh / p.H, hd = bh - b * p.H;
     const int64_t base = b * p.stride_b + hd * p.stride_h;
     const __bf16* Q = (const __bf16*)p.q + base;
     const __bf16* K = (const __bf16*)p.k + base;
@@ -97,7 +92,8 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
         }
 
     u32x4 rk[4];
-    uint32_t rv[16];
+    u32x4 rv[4];
+    const int tr_off = tr_lane_offset(lane);
     load_tile(rk, rv, K, V, 0, tid);
     store_tile(rk, rv, lds, tid);
     __syncthreads();
@@ -159,7 +155,7 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
             for (int g = 0; g < 4; ++g)
 #pragma unroll
                 for (int mb = 0; mb < 4; ++mb)
-                    oacc[mb] = mfma(read_a_trn(stage + K_TILE, 32 * mb + n, g, h), pb[g], oacc[mb]);
+                    oacc[mb] = mfma(read_a_tr(stage + K_TILE, tr_off, g, mb), pb[g], oacc[mb]);
         }
 
         store_tile(rk, rv, lds + ((kt + 1) & 1) * BUF, tid);
@@ -189,7 +185,7 @@ bool fwd_mfma_supported(const StepArgs& a, int dtype) {
 
 hipError_t launch_fwd_mfma(const StepArgs& a, hipStream_t st) {
     const int n_qtiles = a.c / BM;
-    hipLaunchKernelGGL(fwd_mfma_kernel, dim3(n_qtiles, a.B * a.H), dim3(256), 0, st, a, n_qtiles);
+    hipLaunchKernelGGL(fwd_mfma_kernel, dim3(n_qtiles * a.B * a.H), dim3(256), 0, st, a, n_qtiles);
     return hipGetLastError();
 }
 

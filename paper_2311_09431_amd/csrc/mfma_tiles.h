@@ -79,8 +79,58 @@ __device__ inline bf16x8 read_a_trn(const __bf16* lds_tile, int col, int g, int 
     return *reinterpret_cast<const bf16x8*>(lds_tile + col * TS + 16 * g + 8 * h);
 }
 
+// Transposing A-operand reads (ds_read_b64_tr_b16) from a ROW-MAJOR tile whose
+// rows are the contraction index (e.g. V[key][d] for O^T += V^T P^T), row stride
+// XS elements.  Within each block of 16 lanes the instruction hands lane i the
+// i-th 16-bit element of what lanes 4e + i/4 (e = 0..3) point at, so lane j of a
+// block points at row j/4, columns 4 (j%4) .. +3 of a 4 x 16 patch and every
+// lane receives 4 consecutive rows of one column.  Two reads (rows +0 and +8)
+// give the 8 contraction values {0..3, 8..11} + 4h of a group of 16 that match a
+// C/D tile used as B operand.  XS = 128 + 32 keeps both the 16-byte row writes and
+// these 8-byte reads free of bank conflicts (row stride = 16 banks mod 64).
+constexpr int XS = TD + 32;
+constexpr int X_TILE = TR * XS;      // elements
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+__device__ inline void store_rows_x(const u32x4 (&r)[4], __bf16* __restrict__ lds_tile, int tid) {
+    __bf16* p = lds_tile + (tid >> 4) * XS + (tid & 15) * 8;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(p + i * 16 * XS) = r[i];
+}
+// per-lane element offset of the patch this lane points at (group 0, column block 0)
+__device__ inline int tr_lane_offset(int lane) {
+    const int i = lane & 15;
+    return (4 * (lane >> 5) + (i >> 2)) * XS + 16 * ((lane >> 4) & 1) + 4 * (i & 3);
+}
+// A operand for column block mb (32 columns) and row group g (16 rows)
+__device__ inline bf16x8 read_a_tr(const __bf16* lds_tile, int lane_off, int g, int mb) {
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    const __bf16* p = lds_tile + lane_off + 16 * g * XS + 32 * mb;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 8 * XS));
+    const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, both);
+}
+
 __device__ inline f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// Workgroup order of a 1-D grid over (tile rank, batch*head).  Heads are taken in
+// groups of 8; inside a group the index runs over heads fastest and tile ranks
+// slowest, so (i) with rank 0 the heaviest tile, every group runs heaviest-first
+// and the last workgroups to start are the lightest, and (ii) as consecutive
+// workgroups go round-robin to the 8 XCDs, all tiles of one head land on one XCD
+// and share its L2 while they stream the same K/V (or Q/dO) rows.
+constexpr int HEAD_GROUP = 8;
+__device__ inline void decode_block(int linear, int n_tiles, int n_bh, int& rank, int& bh) {
+    const int per_group = HEAD_GROUP * n_tiles;
+    const int grp = linear / per_group;
+    const int within = linear - grp * per_group;
+    const int heads = min(HEAD_GROUP, n_bh - grp * HEAD_GROUP);
+    rank = within / heads;
+    bh = grp * HEAD_GROUP + (within - rank * heads);
 }
 
 // 128-column row of `g` as B-operand fragments: 8 k-steps of 16
