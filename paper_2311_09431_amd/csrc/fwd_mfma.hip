@@ -20,7 +20,8 @@
 // log2(e), l = 1) and leaves as O = acc / l, LSE = (m + log2 l) * ln 2, which is
 // the log-sum-exp merge of the step's partial result with the running one.
 // Row sums are taken over the fp32 probabilities before they are rounded to
-// bf16 for the second product.
+// bf16 for the second product (summing the rounded values costs 1e-3 of LSE
+// accuracy on rows with few keys).
 #include <hip/hip_bf16.h>
 
 #include "mfma_tiles.h"
@@ -46,6 +47,18 @@ __device__ inline void store_tile(const u32x4 (&rk)[4], const u32x4 (&rv)[4],
                                   __bf16* __restrict__ stage, int tid) {
     store_rows(rk, stage, tid);
     store_rows_x(rv, stage + K_TILE, tid);
+}
+
+constexpr float RESCALE_LOG2 = 8.f;
+
+// max over the two half-waves (lanes n and n + 32 hold the same query)
+__device__ inline float half_wave_max(float x) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ inline float half_wave_sum(float x) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
 __global__ void __launch_bounds__(256, 2)
@@ -105,16 +118,30 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
         load_tile(rk, rv, K, V, min(kt + 1, n_kt - 1), tid);
 
         if (kt <= wave_last) {
-            // S^T = K Q^T : two blocks of 32 keys x 32 queries
+            // S^T = K Q^T : two blocks of 32 keys x 32 queries.  All 16 A operands are
+            // requested from LDS before the first MFMA so that the matrix pipe is fed
+            // back to back instead of paying one LDS round trip per pair of MFMAs.
             f32x16 s[2];
+            bf16x8 ka[2][8];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks) ka[kb][ks] = read_a_rows(stage, kb * 32 + n, ks, h);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
 #pragma unroll
-                for (int ks = 0; ks < 8; ++ks)
-                    s[kb] = mfma(read_a_rows(stage, kb * 32 + n, ks, h), qf[ks], s[kb]);
+                for (int ks = 0; ks < 8; ++ks) s[kb] = mfma(ka[kb][ks], qf[ks], s[kb]);
             }
+            // the first half of the V operands travels while the softmax runs
+            bf16x8 va[4][4];
+#pragma unroll
+            for (int g = 0; g < 2; ++g)
+#pragma unroll
+                for (int mb = 0; mb < 4; ++mb) va[g][mb] = read_a_tr(stage + K_TILE, tr_off, g, mb);
+            __builtin_amdgcn_sched_barrier(0);
             // element mask, only on tiles crossing the diagonal: allowed iff key <= a - off
             if (tri && kt * BN + BN - 1 > a_lo - off) {
                 const int lim = a - off - kt * BN - 4 * h;   // allowed iff 8*(r/4) + r%4 + 32 kb <= lim
@@ -124,38 +151,53 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
                     for (int r = 0; r < 16; ++r)
                         if (32 * kb + 8 * (r / 4) + (r % 4) > lim) s[kb][r] = -INFINITY;
             }
-            // online softmax, base 2
+            // online softmax, base 2, with a lazily updated reference m: the reference
+            // moves only when a row's tile maximum exceeds it by more than 2^RESCALE_LOG2,
+            // so p <= 2^RESCALE_LOG2 (harmless in bf16 / fp32) and the rescaling of l and
+            // of the 64 accumulator registers is skipped on almost every tile.
             float mx = s[0][0];
 #pragma unroll
             for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[0][r]);
 #pragma unroll
             for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[1][r]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m, mx * kappa);
-            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;   // row with no key so far
-            const float alpha = __builtin_amdgcn_exp2f(m - m_use);
-            m = m_new;
-            float rs = 0.f;
+            mx = half_wave_max(mx);
+            const float cand = mx * kappa;
+            if (__builtin_amdgcn_ballot_w64(cand > m + RESCALE_LOG2) != 0) {     // wave-uniform
+                const float m_new = fmaxf(m, cand);
+                const float alpha = __builtin_amdgcn_exp2f(m - ((m_new == -INFINITY) ? 0.f : m_new));
+                m = m_new;
+                l *= alpha;
+#pragma unroll
+                for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) oacc[mb][r] *= alpha;
+            }
+            const float m_use = (m == -INFINITY) ? 0.f : m;       // row with no key so far
             bf16x8 pb[4];
+            float rs0 = 0.f, rs1 = 0.f;
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float pr = __builtin_amdgcn_exp2f(fmaf(s[kb][r], kappa, -m_use));
-                    rs += pr;
-                    pb[2 * kb + r / 8][r % 8] = (__bf16)pr;
+                for (int r = 0; r < 16; r += 2) {
+                    const float p0 = __builtin_amdgcn_exp2f(fmaf(s[kb][r], kappa, -m_use));
+                    const float p1 = __builtin_amdgcn_exp2f(fmaf(s[kb][r + 1], kappa, -m_use));
+                    rs0 += p0;                 // row sums in fp32, before the rounding to bf16
+                    rs1 += p1;
+                    pb[2 * kb + r / 8][r % 8] = (__bf16)p0;
+                    pb[2 * kb + r / 8][r % 8 + 1] = (__bf16)p1;
                 }
-            l = l * alpha + rs;
-#pragma unroll
-            for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[mb][r] *= alpha;
+            l += rs0 + rs1;
             // O^T += V^T P^T : 4 blocks of 32 d-rows, 4 k-steps of 16 keys
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int g = 2; g < 4; ++g)
+#pragma unroll
+                for (int mb = 0; mb < 4; ++mb) va[g][mb] = read_a_tr(stage + K_TILE, tr_off, g, mb);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int g = 0; g < 4; ++g)
 #pragma unroll
-                for (int mb = 0; mb < 4; ++mb)
-                    oacc[mb] = mfma(read_a_tr(stage + K_TILE, tr_off, g, mb), pb[g], oacc[mb]);
+                for (int mb = 0; mb < 4; ++mb) oacc[mb] = mfma(va[g][mb], pb[g], oacc[mb]);
         }
 
         store_tile(rk, rv, lds + ((kt + 1) & 1) * BUF, tid);
@@ -163,7 +205,7 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     }
 
     // epilogue: normalise, store the merged state
-    const float l_tot = l + __shfl_xor(l, 32);
+    const float l_tot = half_wave_sum(l);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb)
