@@ -1,28 +1,50 @@
 // Forward ring step on the CDNA4 matrix cores (bf16 operands, fp32 accumulate),
 // head dimension 128: AccumulateAttentionFragment of Algorithm 1 with the fused
-// log-sum-exp merge, skipping every key tile that GetMask(j, k) masks entirely
-// (Sec. 2.2.1) at a 64-key granularity per 32-query wavefront.
+// log-sum-exp merge, skipping every 32-key sub-tile that GetMask(j, k) masks
+// entirely for a 32-query wavefront (Sec. 2.2.1).
 //
 // Work decomposition.  A workgroup of 4 wavefronts owns 128 query rows; each
 // wavefront owns 32 of them for the whole kernel.  Key/value tiles of 64 rows
-// stream through LDS, double buffered (one barrier per tile).
+// stream from global memory straight into LDS (global_load_lds, no register
+// staging), two buffers each for K and V, one barrier per tile.
 //
 // The scores are computed TRANSPOSED, S^T = K Q^T (A = key rows from LDS, B = the
-// query rows, resident in registers), so that a lane holds 16 + 16 keys of ONE
-// query: the row max / row sum of the online softmax are in-lane reductions
-// plus a single exchange between the two half-waves, and the probabilities
-// already sit in the B-operand layout of the second product O^T += V^T P^T.
-// Its A operand, V^T, is read from the row-major V tile with the transposing
-// LDS read, so both tiles are staged with plain 16-byte copies.
+// query rows, resident in registers), so that a lane holds 16 keys of ONE query
+// per 32-key sub-tile: row max / row sum of the online softmax are in-lane
+// reductions plus one exchange between the two half-waves, and the
+// probabilities already sit in the B-operand layout of the second product
+// O^T += V^T P^T, whose A operand is read from the row-major V tile with the
+// transposing LDS read.
 //
-// Online softmax in base 2: kappa = scale * log2(e) is folded into the exponent,
-// p = exp2(s * kappa - m).  The running state enters as (acc = O, m = LSE *
-// log2(e), l = 1) and leaves as O = acc / l, LSE = (m + log2 l) * ln 2, which is
-// the log-sum-exp merge of the step's partial result with the running one.
-// Row sums are taken over the fp32 probabilities before they are rounded to
-// bf16 for the second product (summing the rounded values costs 1e-3 of LSE
-// accuracy on rows with few keys).
+// Software pipeline.  MFMA and VALU instructions only overlap when they are
+// interleaved in one wavefront's instruction stream, so the loop runs over
+// 32-key sub-tiles u with three stages in flight:
+//     S(u+1) = K(u+1) Q^T   (8 MFMA)   |
+//     P(u)   = softmax part of S(u)    |  issued interleaved, slice by slice
+//     O^T   += V(u-1)^T P(u-1) (8 MFMA)|
+// i.e. one exp2 and about three other VALU instructions per MFMA.
+//
+// Online softmax in base 2 with a lazily updated reference m: kappa = scale *
+// log2(e) is folded into the exponent, p = exp2(s * kappa - m), and m moves
+// only when a row's sub-tile maximum exceeds it by more than 2^RESCALE_LOG2, so
+// the rescaling of l, of the 64 accumulator registers and of the pending
+// probabilities almost never runs.  The running
+// state enters as (acc = O, m = LSE * log2(e), l = 1) and leaves as O = acc / l,
+// LSE = (m + log2 l) * ln 2, which is the log-sum-exp merge of the step's
+// partial result with the running one.  Row sums are taken over the fp32
+// probabilities before they are rounded to bf16 (summing the rounded values
+// costs 1e-3 of LSE accuracy on rows with few keys).
+//
+// LDS layout.  Both tiles are 64 rows x 256 bytes without padding (the direct
+// loads write 1 KiB per wavefront contiguously); bank conflicts are avoided by
+// XOR-swizzling the 16-byte chunk index with the row: K chunk c of row r sits at
+// chunk c ^ (r & 15) (16-byte A-operand reads of 16 consecutive rows hit 16
+// different chunks), V chunk c of row r at c ^ ((r & 3) << 2) (the 4-row x 32-byte
+// patches of the transposing read hit different 32-byte bank groups).  The
+// swizzle is applied by choosing which global chunk each lane loads.
 #include <hip/hip_bf16.h>
+
+#include <type_traits>
 
 #include "mfma_tiles.h"
 #include "sa_internal.h"
@@ -31,27 +53,20 @@ namespace sa {
 
 namespace {
 
-constexpr int BM = 128;        // query rows per workgroup
-constexpr int BN = TR;         // key rows per tile
-constexpr int D = TD;          // head dimension
-constexpr int K_TILE = ROW_TILE;
-constexpr int BUF = ROW_TILE + X_TILE;        // elements per pipeline stage: K rows, V rows
-
-// Global -> registers and registers -> LDS stage for key tile kt.
-__device__ inline void load_tile(u32x4 (&rk)[4], u32x4 (&rv)[4], const __bf16* __restrict__ K,
-                                 const __bf16* __restrict__ V, int kt, int tid) {
-    load_rows(rk, K + (int64_t)kt * BN * D, tid);
-    load_rows(rv, V + (int64_t)kt * BN * D, tid);
-}
-__device__ inline void store_tile(const u32x4 (&rk)[4], const u32x4 (&rv)[4],
-                                  __bf16* __restrict__ stage, int tid) {
-    store_rows(rk, stage, tid);
-    store_rows_x(rv, stage + K_TILE, tid);
-}
-
+constexpr int BM = 128;                 // query rows per workgroup
+constexpr int D = TD;                   // head dimension
+constexpr int TILE_ROWS = 64;           // key rows per LDS tile
+constexpr int TILE_BYTES = TILE_ROWS * D * 2;   // 16 KiB
+constexpr int K_BUF0 = 0;               // two K tiles, then two V tiles
+constexpr int V_BUF0 = 2 * TILE_BYTES;
+constexpr int LDS_BYTES = 4 * TILE_BYTES;
 constexpr float RESCALE_LOG2 = 8.f;
 
-// max over the two half-waves (lanes n and n + 32 hold the same query)
+typedef __attribute__((address_space(3))) char lds_char;
+typedef __attribute__((address_space(1))) const char global_char;
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+// max / sum over the two half-waves (lanes n and n + 32 hold the same query)
 __device__ inline float half_wave_max(float x) {
     const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
     return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
@@ -61,36 +76,155 @@ __device__ inline float half_wave_sum(float x) {
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
+// One tile (64 rows) of K or V: 16 KiB = 16 wavefront loads of 1 KiB, 4 per wavefront.
+// g[j]: this lane's byte offset into the tile for its j-th load.
+__device__ inline void load_tile_direct(const char* __restrict__ gtile, char* lds_tile, const uint32_t (&g)[4],
+                                        int wave) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        __builtin_amdgcn_global_load_lds((global_char*)(gtile + g[j]), (lds_char*)(lds_tile + (4 * wave + j) * 1024),
+                                         16, 0, 0);
+}
+
+__device__ inline bf16x8 lds_read_b128(const char* lds, uint32_t addr) {
+    return *reinterpret_cast<const bf16x8*>(lds + addr);
+}
+__device__ inline bf16x8 lds_read_tr(const char* lds, uint32_t addr) {
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(lds + addr));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(lds + addr + 8 * 256));
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+// One pipeline step on sub-tile u (32 keys):
+//   QK: s_next = K(u+1) Q^T            k_next = LDS address of the 32 K rows of sub-tile u+1
+//   SM: p_cur = exp2(s_cur * kappa - m), with the lazy reference update
+//   PV: oacc += V(u-1)^T p_prev        v_prev = LDS address of the 32 V rows of sub-tile u-1
+// MASK applies the element mask to s_cur: register r (key 8 (r/4) + 4h + r%4 of the
+// sub-tile) is allowed iff 8 (r/4) + r%4 <= mask_lim (mask_lim already holds -4h).
+template <bool QK, bool SM, bool PV, bool MASK>
+__device__ inline void step(f32x16& s_cur, f32x16& s_next, bf16x8 (&p_cur)[2], bf16x8 (&p_prev)[2],
+                            f32x16 (&oacc)[4], const bf16x8 (&qf)[8], float& m, float& l, float kappa,
+                            const uint32_t (&kaddr)[8], const uint32_t (&vaddr)[4], const char* k_next,
+                            const char* v_prev, int mask_lim) {
+    // Operands of slice i are requested from LDS two slices ahead, so only a few of
+    // them are live at a time; slice i holds QK MFMA i (k-step i) and PV MFMA i
+    // (16-key group i / 4, 32-column block i % 4).
+    bf16x8 ka[8], va[8];
+    auto fetch = [&](int i) {
+        if (QK) ka[i] = lds_read_b128(k_next, kaddr[i]);
+        if (PV) va[i] = lds_read_tr(v_prev + (i / 4) * 16 * 256, vaddr[i % 4]);
+    };
+    fetch(0);
+    fetch(1);
+    float m_use = 0.f;
+    if (SM) {
+        if (MASK) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                if (8 * (r / 4) + (r % 4) > mask_lim) s_cur[r] = -INFINITY;
+        }
+        float mx = fmaxf(s_cur[0], s_cur[1]);
+#pragma unroll
+        for (int r = 2; r < 16; ++r) mx = fmaxf(mx, s_cur[r]);
+        mx = half_wave_max(mx);
+        const float cand = mx * kappa;
+        if (__builtin_amdgcn_ballot_w64(cand > m + RESCALE_LOG2) != 0) {      // wave-uniform, rare
+            const float m_new = fmaxf(m, cand);
+            const float alpha = __builtin_amdgcn_exp2f(m - ((m_new == -INFINITY) ? 0.f : m_new));
+            m = m_new;
+            l *= alpha;
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[mb][r] *= alpha;
+            if (PV) {   // the pending probabilities were taken against the old reference
+#pragma unroll
+                for (int g = 0; g < 2; ++g)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) p_prev[g][e] = (__bf16)(alpha * (float)p_prev[g][e]);
+            }
+        }
+        m_use = (m == -INFINITY) ? 0.f : m;        // row with no key so far
+    }
+    if (QK) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s_next[r] = 0.f;
+    }
+    float rs0 = 0.f, rs1 = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        __builtin_amdgcn_sched_barrier(0);         // slices stay in program order
+        if (i + 2 < 8) fetch(i + 2);
+        if (QK) s_next = mfma(ka[i], qf[i], s_next);
+        if (PV) oacc[i % 4] = mfma(va[i], p_prev[i / 4], oacc[i % 4]);
+        if (SM) {
+            const float p0 = __builtin_amdgcn_exp2f(fmaf(s_cur[2 * i], kappa, -m_use));
+            const float p1 = __builtin_amdgcn_exp2f(fmaf(s_cur[2 * i + 1], kappa, -m_use));
+            rs0 += p0;
+            rs1 += p1;
+            p_cur[i / 4][(2 * i) % 8] = (__bf16)p0;
+            p_cur[i / 4][(2 * i) % 8 + 1] = (__bf16)p1;
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (SM) l += rs0 + rs1;
+}
+
+template <bool TRI>
 __global__ void __launch_bounds__(256, 2)
 fwd_mfma_kernel(StepArgs p, int n_qtiles) {
-    __shared__ __attribute__((aligned(16))) __bf16 lds[2 * BUF];
+    __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, h = lane >> 5;
-    const bool tri = p.kind == MASK_TRI;
+    const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, h = lane >> 5, wave = tid >> 6;
     int rank, bh;
     decode_block((int)blockIdx.x, n_qtiles, p.B * p.H, rank, bh);
-    const int qt = tri ? n_qtiles - 1 - rank : rank;      // triangular steps: heaviest query tiles first
+    const int qt = TRI ? n_qtiles - 1 - rank : rank;      // triangular steps: heaviest query tiles first
     const int b = bh / p.H, hd = bh - b * p.H;
     const int64_t base = b * p.stride_b + hd * p.stride_h;
     const __bf16* Q = (const __bf16*)p.q + base;
-    const __bf16* K = (const __bf16*)p.k + base;
-    const __bf16* V = (const __bf16*)p.v + base;
+    const char* K = (const char*)((const __bf16*)p.k + base);
+    const char* V = (const char*)((const __bf16*)p.v + base);
     float* O = p.o + base;
     float* L = p.lse + b * p.stat_stride_b + hd * p.stat_stride_h;
 
     const int q0 = qt * BM;
-    const int a_lo = q0 + 32 * wave;          // first query row of this wavefront
-    const int a = a_lo + n;                   // this lane's query row
-    const int off = p.off;
-    // key tiles holding at least one allowed pair: for the workgroup / for this wavefront
-    const int n_kt = tri ? min(p.c / BN, (q0 + BM - 1 - off) / BN + 1) : p.c / BN;
-    const int wave_last = tri ? (a_lo + 31 - off) / BN : n_kt - 1;
+    const int a = q0 + 32 * wave + n;         // this lane's query row
+    // 64-key tiles holding at least one allowed pair for the workgroup.  Triangular: keys
+    // b <= a - off, i.e. tiles 0 .. (q0 + 127) / 64.  All four wavefronts walk all 2 n_kt
+    // sub-tiles (at most three of them are entirely masked for a wavefront); the element
+    // mask is applied on the last four sub-tiles only.
+    const int n_kt = TRI ? (q0 + BM) / TILE_ROWS : p.c / TILE_ROWS;
+    // sub-tile v: register r (key 32 v + 8 (r/4) + 4h + r%4) is allowed iff
+    // 8 (r/4) + r%4 <= mask_base - 32 v
+    const int mask_base = a - p.off - 4 * h;
 
-    // query rows as B operands: 8 k-steps of 16
+    // per-lane addresses: K A-operand reads per k-step, V transposing reads per 32-column
+    // block (bytes within a 32-row half tile), and the global byte offsets of this lane's
+    // direct loads
+    uint32_t kaddr[8], vaddr[4], kg[4], vg[4];
+    {
+        const int x = n & 15;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) kaddr[ks] = n * 256 + (((2 * ks + h) ^ x) << 4);
+        const int i = lane & 15, nh = (lane >> 4) & 1, j4 = i >> 2;
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb)
+            vaddr[mb] = (4 * h + j4) * 256 + ((4 * (mb ^ j4) + 2 * nh + ((i & 3) >> 1)) << 4) + (i & 1) * 8;
+        const int lr = lane >> 4, pc = lane & 15;      // row within the 4-row group, physical chunk
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            kg[j] = (16 * wave + 4 * j + lr) * 256 + ((pc ^ (4 * j + lr)) << 4);
+            vg[j] = (16 * wave + 4 * j + lr) * 256 + ((pc ^ (lr << 2)) << 4);
+        }
+    }
+
+    // first tiles on their way while the running state is loaded
+    load_tile_direct(K, lds + K_BUF0, kg, wave);
+    load_tile_direct(V, lds + V_BUF0, vg, wave);
+    load_tile_direct(K + TILE_BYTES, lds + K_BUF0 + TILE_BYTES, kg, wave);     // n_kt >= 2 always
+
     bf16x8 qf[8];
     load_b_frags(qf, Q + (int64_t)a * D, h);
-
-    // running state -> accumulators
     const float kappa = p.scale * LOG2E;
     float m = L[a] * LOG2E;                   // -inf stays -inf
     float l = (h == 0) ? 1.f : 0.f;           // the two half-waves hold partial row sums
@@ -104,104 +238,88 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
             oacc[mb][4 * g + 2] = x.z; oacc[mb][4 * g + 3] = x.w;
         }
 
-    u32x4 rk[4];
-    u32x4 rv[4];
-    const int tr_off = tr_lane_offset(lane);
-    load_tile(rk, rv, K, V, 0, tid);
-    store_tile(rk, rv, lds, tid);
-    __syncthreads();
+    __builtin_amdgcn_s_waitcnt(0);     // the direct loads have landed (vmcnt) ...
+    __syncthreads();                   // ... for every wavefront
 
-    for (int kt = 0; kt < n_kt; ++kt) {
-        const __bf16* stage = lds + (kt & 1) * BUF;
-        // prefetch the next tile into registers (the last iteration re-reads its own
-        // tile into the idle stage, which keeps the loop free of branches)
-        load_tile(rk, rv, K, V, min(kt + 1, n_kt - 1), tid);
+    f32x16 s_a, s_b;
+    bf16x8 p_a[2], p_b[2];
+#pragma unroll
+    for (int g = 0; g < 2; ++g)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) p_a[g][e] = p_b[g][e] = (__bf16)0.f;
+    // prologue: S(0)
+    {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s_a[r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) s_a = mfma(lds_read_b128(lds + K_BUF0, kaddr[ks]), qf[ks], s_a);
+    }
 
-        if (kt <= wave_last) {
-            // S^T = K Q^T : two blocks of 32 keys x 32 queries.  All 16 A operands are
-            // requested from LDS before the first MFMA so that the matrix pipe is fed
-            // back to back instead of paying one LDS round trip per pair of MFMAs.
-            f32x16 s[2];
-            bf16x8 ka[2][8];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int ks = 0; ks < 8; ++ks) ka[kb][ks] = read_a_rows(stage, kb * 32 + n, ks, h);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
-#pragma unroll
-                for (int ks = 0; ks < 8; ++ks) s[kb] = mfma(ka[kb][ks], qf[ks], s[kb]);
-            }
-            // the first half of the V operands travels while the softmax runs
-            bf16x8 va[4][4];
-#pragma unroll
-            for (int g = 0; g < 2; ++g)
-#pragma unroll
-                for (int mb = 0; mb < 4; ++mb) va[g][mb] = read_a_tr(stage + K_TILE, tr_off, g, mb);
-            __builtin_amdgcn_sched_barrier(0);
-            // element mask, only on tiles crossing the diagonal: allowed iff key <= a - off
-            if (tri && kt * BN + BN - 1 > a_lo - off) {
-                const int lim = a - off - kt * BN - 4 * h;   // allowed iff 8*(r/4) + r%4 + 32 kb <= lim
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        if (32 * kb + 8 * (r / 4) + (r % 4) > lim) s[kb][r] = -INFINITY;
-            }
-            // online softmax, base 2, with a lazily updated reference m: the reference
-            // moves only when a row's tile maximum exceeds it by more than 2^RESCALE_LOG2,
-            // so p <= 2^RESCALE_LOG2 (harmless in bf16 / fp32) and the rescaling of l and
-            // of the 64 accumulator registers is skipped on almost every tile.
-            float mx = s[0][0];
-#pragma unroll
-            for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[0][r]);
-#pragma unroll
-            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[1][r]);
-            mx = half_wave_max(mx);
-            const float cand = mx * kappa;
-            if (__builtin_amdgcn_ballot_w64(cand > m + RESCALE_LOG2) != 0) {     // wave-uniform
-                const float m_new = fmaxf(m, cand);
-                const float alpha = __builtin_amdgcn_exp2f(m - ((m_new == -INFINITY) ? 0.f : m_new));
-                m = m_new;
-                l *= alpha;
-#pragma unroll
-                for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) oacc[mb][r] *= alpha;
-            }
-            const float m_use = (m == -INFINITY) ? 0.f : m;       // row with no key so far
-            bf16x8 pb[4];
-            float rs0 = 0.f, rs1 = 0.f;
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; r += 2) {
-                    const float p0 = __builtin_amdgcn_exp2f(fmaf(s[kb][r], kappa, -m_use));
-                    const float p1 = __builtin_amdgcn_exp2f(fmaf(s[kb][r + 1], kappa, -m_use));
-                    rs0 += p0;                 // row sums in fp32, before the rounding to bf16
-                    rs1 += p1;
-                    pb[2 * kb + r / 8][r % 8] = (__bf16)p0;
-                    pb[2 * kb + r / 8][r % 8 + 1] = (__bf16)p1;
-                }
-            l += rs0 + rs1;
-            // O^T += V^T P^T : 4 blocks of 32 d-rows, 4 k-steps of 16 keys
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int g = 2; g < 4; ++g)
-#pragma unroll
-                for (int mb = 0; mb < 4; ++mb) va[g][mb] = read_a_tr(stage + K_TILE, tr_off, g, mb);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int g = 0; g < 4; ++g)
-#pragma unroll
-                for (int mb = 0; mb < 4; ++mb) oacc[mb] = mfma(va[g][mb], pb[g], oacc[mb]);
-        }
-
-        store_tile(rk, rv, lds + ((kt + 1) & 1) * BUF, tid);
+    // Trip t = iterations u = 2t and 2t+1 with barrier t between them.  Iteration u does
+    // QK(u+1), softmax(u), PV(u-1); S(even) lives in s_a, S(odd) in s_b, P likewise.
+    //   u = 2t:   QK(2t+1): K tile t, second half      PV(2t-1): V tile t-1, second half
+    //   barrier t: K tile t and V tile t-1 are free -> load K(t+2), V(t+1); K(t+1), V(t),
+    //              requested at barrier t-1, have landed
+    //   u = 2t+1: QK(2t+2): K tile t+1, first half     PV(2t): V tile t, first half
+    // PAR = t & 1 fixes every LDS offset at compile time.
+    auto trip = [&](auto first_c, auto last_c, auto mask_c, auto par_c, int t) {
+        constexpr bool FIRST = decltype(first_c)::value, LAST = decltype(last_c)::value;
+        constexpr bool MASK = decltype(mask_c)::value;
+        constexpr int PAR = decltype(par_c)::value;
+        const char* k_cur = lds + K_BUF0 + PAR * TILE_BYTES;
+        const char* k_nxt = lds + K_BUF0 + (PAR ^ 1) * TILE_BYTES;
+        const char* v_cur = lds + V_BUF0 + PAR * TILE_BYTES;
+        const char* v_prv = lds + V_BUF0 + (PAR ^ 1) * TILE_BYTES;
+        step<true, true, !FIRST, MASK>(s_a, s_b, p_a, p_b, oacc, qf, m, l, kappa, kaddr, vaddr,
+                                       k_cur + TILE_BYTES / 2, v_prv + TILE_BYTES / 2, mask_base - 64 * t);
+        __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
+        if (t + 2 < n_kt) load_tile_direct(K + (int64_t)(t + 2) * TILE_BYTES, lds + K_BUF0 + PAR * TILE_BYTES, kg, wave);
+        if (t + 1 < n_kt) load_tile_direct(V + (int64_t)(t + 1) * TILE_BYTES, lds + V_BUF0 + (PAR ^ 1) * TILE_BYTES, vg, wave);
+        step<!LAST, true, true, MASK>(s_b, s_a, p_b, p_a, oacc, qf, m, l, kappa, kaddr, vaddr, k_nxt, v_cur,
+                                      mask_base - 64 * t - 32);
+    };
+    using T = std::true_type;
+    using F = std::false_type;
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    // masked trips (triangular only): the last two, n_kt - 2 and n_kt - 1
+    const int n_plain = TRI ? n_kt - 2 : n_kt;       // trips 0 .. n_plain - 1 run without the element mask
+    int t = 0;
+    if (n_plain >= 1) {
+        if (!TRI && n_kt == 1) { /* unreachable: c >= 128 */ }
+        trip(T{}, F{}, F{}, P0{}, 0);
+        t = 1;
+        const int t_end = TRI ? n_plain : n_kt - 1;   // full steps keep the last trip for the LAST variant
+        for (; t + 1 < t_end; t += 2) {
+            trip(F{}, F{}, F{}, P1{}, t);
+            trip(F{}, F{}, F{}, P0{}, t + 1);
+        }
+        if (t < t_end) {
+            trip(F{}, F{}, F{}, P1{}, t);
+            ++t;
+        }
+    }
+    if (TRI) {
+        // t == n_kt - 2 (or 0 when n_kt == 2): two masked trips, the second one is the last
+        if (t == 0) {
+            trip(T{}, F{}, T{}, P0{}, 0);
+            trip(F{}, T{}, T{}, P1{}, 1);
+        } else if (t & 1) {
+            trip(F{}, F{}, T{}, P1{}, t);
+            trip(F{}, T{}, T{}, P0{}, t + 1);
+        } else {
+            trip(F{}, F{}, T{}, P0{}, t);
+            trip(F{}, T{}, T{}, P1{}, t + 1);
+        }
+    } else {
+        if (t & 1) trip(F{}, T{}, F{}, P1{}, t);
+        else trip(F{}, T{}, F{}, P0{}, t);
+    }
+    // final iteration u = 2 n_kt: PV(2 n_kt - 1): V tile n_kt - 1, second half; P in p_b
+    {
+        const char* v_last = lds + V_BUF0 + ((n_kt - 1) & 1) * TILE_BYTES + TILE_BYTES / 2;
+        step<false, false, true, false>(s_a, s_b, p_a, p_b, oacc, qf, m, l, kappa, kaddr, vaddr, v_last, v_last, 0);
     }
 
     // epilogue: normalise, store the merged state
@@ -227,7 +345,10 @@ bool fwd_mfma_supported(const StepArgs& a, int dtype) {
 
 hipError_t launch_fwd_mfma(const StepArgs& a, hipStream_t st) {
     const int n_qtiles = a.c / BM;
-    hipLaunchKernelGGL(fwd_mfma_kernel, dim3(n_qtiles * a.B * a.H), dim3(256), 0, st, a, n_qtiles);
+    if (a.kind == MASK_TRI)
+        hipLaunchKernelGGL(fwd_mfma_kernel<true>, dim3(n_qtiles * a.B * a.H), dim3(256), 0, st, a, n_qtiles);
+    else
+        hipLaunchKernelGGL(fwd_mfma_kernel<false>, dim3(n_qtiles * a.B * a.H), dim3(256), 0, st, a, n_qtiles);
     return hipGetLastError();
 }
 
