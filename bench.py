@@ -30,6 +30,9 @@ from paper_2311_09431_amd import inputs           # noqa: E402
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this workload
+# (see profiles/); None until measured for a kernel
+TRAFFIC = {}
 
 # one device's share: the worst-loaded query device of both layouts is N-1
 WORKLOADS = {
@@ -145,7 +148,7 @@ def main():
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="cfg3", choices=sorted(WORKLOADS))
-    ap.add_argument("--bwd", type=int, default=0, help="1: include the backward ring in the pass")
+    ap.add_argument("--bwd", type=int, default=1, help="0: forward ring only (default: forward + backward)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=3)
     args = ap.parse_args()
@@ -191,18 +194,21 @@ def main():
         ctab_b.append(tb)
     contig_rows, contig_worst = summarize_steps(w, sa.CONTIGUOUS, avg(ctab_f), 4)
 
-    # roofline of the dominant kernel (the forward MFMA step; the backward step when on):
-    # algorithmic flops of one launch / its average HIP-event duration
+    # roofline per kernel family: algorithmic flops of one launch / its average HIP-event
+    # duration (events recorded by the ring driver on the launch stream); the dominant one
+    # (largest share of the pass) is reported as "roofline"
+    def roof(rows, name):
+        live = [r for r in rows if r["ms"] > 0]
+        tot_ms = sum(r["ms"] for r in live)
+        ach = sum(r["tflops"] * r["ms"] for r in live) / max(1e-9, tot_ms)
+        return dict(bound="mfma", kernel=name, achieved=round(ach, 1), peak=PEAK_BF16_TFLOPS,
+                    unit="TFLOP/s", frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=TRAFFIC.get(name),
+                    avg_launch_ms=round(tot_ms / max(1, len(live)), 4), total_ms=round(tot_ms, 3))
+    roofs = {"fwd": roof(striped_rows, "fwd ring step (fwd_mfma_kernel)")}
     if args.bwd:
-        rows_dom, _ = summarize_steps(w, sa.STRIPED, avg(tables_b), 10)
-        dom_name = "bwd ring step"
-    else:
-        rows_dom, dom_name = striped_rows, "fwd ring step"
-    live = [r for r in rows_dom if r["ms"] > 0]
-    ach = sum(r["tflops"] * r["ms"] for r in live) / max(1e-9, sum(r["ms"] for r in live))
-    roofline = dict(bound="mfma", kernel=dom_name, achieved=round(ach, 1), peak=PEAK_BF16_TFLOPS,
-                    unit="TFLOP/s", frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=None,
-                    avg_launch_ms=round(sum(r["ms"] for r in live) / max(1, len(live)), 4))
+        rows_b, _ = summarize_steps(w, sa.STRIPED, avg(tables_b), 10)
+        roofs["bwd"] = roof(rows_b, "bwd ring step (bwd_dq_mfma_kernel + bwd_dkdv_mfma_kernel)")
+    roofline = max(roofs.values(), key=lambda r: r["total_ms"])
 
     result = {
         "metric": "useful causal TFLOP/s per ring step (striped layout, worst-loaded device's share)",
@@ -214,6 +220,7 @@ def main():
                    "pass": "stripe_permute + ring fwd" + (" + ring bwd" if args.bwd else "") + " + finalize"},
         "frac_of_bf16_peak": round(value / PEAK_BF16_TFLOPS, 4),
         "roofline": roofline,
+        "roofline_by_kernel": roofs,
         "striped": {"worst_device_ms_per_round": striped_worst, "ring_sum_ms": round(sum(striped_worst), 4),
                     "steps": striped_rows},
         "contiguous": {"worst_device_ms_per_round": contig_worst, "ring_sum_ms": round(sum(contig_worst), 4),
