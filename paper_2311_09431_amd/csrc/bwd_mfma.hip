@@ -19,6 +19,8 @@
 // apply the element mask only on tiles that cross the diagonal.
 #include <hip/hip_bf16.h>
 
+#include <type_traits>
+
 #include "mfma_tiles.h"
 #include "sa_internal.h"
 
@@ -38,32 +40,95 @@ __device__ inline bf16x8 pack8(const f32x16& x, int first) {
 }
 
 // ---------------------------------------------------------------- dQ kernel
-constexpr int DQ_K = 0;                       // K rows
-constexpr int DQ_KT = ROW_TILE;               // K transposed
-constexpr int DQ_V = ROW_TILE + TRN_TILE;     // V rows
-constexpr int DQ_LDS = 2 * ROW_TILE + TRN_TILE;
+// K and V tiles (64 key rows) stream global -> LDS directly into swizzled tiles, two
+// buffers each.  The loop runs over 32-key sub-tiles u; iteration u issues, interleaved
+// slice by slice,
+//     S^T(u+1) = K(u+1) Q^T, dP^T(u+1) = V(u+1) dO^T   (16 MFMA)
+//     P(u) = exp2(S(u) kappa - LSE), dS(u) = P (dP(u) - delta)   (VALU)
+// and then dQ^T += K(u)^T dS(u)^T (8 MFMA, K^T through the transposing LDS read).
+// Two barriers per 64-key tile: one makes the tile requested one iteration earlier
+// visible, one releases the tile just finished for the next request.
+constexpr int DQ_LDS_BYTES = 4 * DT_BYTES;       // K0, K1, V0, V1
 
+template <bool NEXT, bool MASK>
+__device__ inline void dq_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, f32x16& dp_next,
+                               f32x16 (&acc)[4], const bf16x8 (&qf)[8], const bf16x8 (&gf)[8],
+                               float kappa, float lse2, float delta, const uint32_t (&arow)[8],
+                               const uint32_t (&tr0)[4], const uint32_t (&tr1)[4],
+                               const char* k_next, const char* v_next, const char* k_cur, int mask_lim) {
+    bf16x8 ka[8], va[8], kt[8], dsb[2];
+    auto fetch = [&](int i) {
+        if (NEXT) {
+            ka[i] = dt_read_row(k_next, arow[i]);
+            va[i] = dt_read_row(v_next, arow[i]);
+        }
+    };
+    auto fetch_t = [&](int i) { kt[i] = dt_read_tr(k_cur + (i / 4) * 16 * 256, tr0[i % 4], tr1[i % 4]); };
+    fetch(0);
+    fetch(1);
+    if (NEXT) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s_next[r] = dp_next[r] = 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        __builtin_amdgcn_sched_barrier(0);          // slices stay in program order
+        if (i + 2 < 8) fetch(i + 2);
+        if (i >= 4) fetch_t(i - 4);                 // first half of the K^T operands
+        if (NEXT) {
+            s_next = mfma(ka[i], qf[i], s_next);
+            dp_next = mfma(va[i], gf[i], dp_next);
+        }
+#pragma unroll
+        for (int r = 2 * i; r < 2 * i + 2; ++r) {
+            float pr = __builtin_amdgcn_exp2f(fmaf(s_cur[r], kappa, -lse2));
+            if (MASK && 8 * (r / 4) + (r % 4) > mask_lim) pr = 0.f;
+            dsb[r / 8][r % 8] = (__bf16)(pr * (dp_cur[r] - delta));
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        if (i + 4 < 8) fetch_t(i + 4);
+        acc[i % 4] = mfma(kt[i], dsb[i / 4], acc[i % 4]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+template <bool TRI>
 __global__ void __launch_bounds__(256, 2)
 bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
-    __shared__ __attribute__((aligned(16))) __bf16 lds[DQ_LDS];
+    __shared__ __attribute__((aligned(1024))) char lds[DQ_LDS_BYTES];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, h = lane >> 5;
-    const bool tri = p.kind == MASK_TRI;
     int rank, bh;
     decode_block((int)blockIdx.x, n_tiles, p.B * p.H, rank, bh);
-    const int qt = tri ? n_tiles - 1 - rank : rank;      // heaviest query tiles first
+    const int qt = TRI ? n_tiles - 1 - rank : rank;      // heaviest query tiles first
     const int b = bh / p.H, hd = bh - b * p.H;
     const int64_t base = b * p.stride_b + hd * p.stride_h;
     const int64_t sbase = b * p.stat_stride_b + hd * p.stat_stride_h;
     const __bf16* Q = (const __bf16*)p.q + base;
-    const __bf16* K = (const __bf16*)p.k + base;
-    const __bf16* V = (const __bf16*)p.v + base;
+    const char* K = (const char*)((const __bf16*)p.k + base);
+    const char* V = (const char*)((const __bf16*)p.v + base);
     const __bf16* G = (const __bf16*)p.dout + base;
     float* DQ = p.dq + base;
 
-    const int q0 = qt * BM, a_lo = q0 + 32 * wave, a = a_lo + n, off = p.off;
-    const int n_kt = tri ? min(p.c / BN, (q0 + BM - 1 - off) / BN + 1) : p.c / BN;
-    const int wave_last = tri ? (a_lo + 31 - off) / BN : n_kt - 1;
+    const int q0 = qt * BM, a = q0 + 32 * wave + n;
+    // all four wavefronts walk the 2 n_kt sub-tiles of the workgroup (at most three are
+    // entirely masked for a wavefront); the element mask runs on the last four only
+    const int n_kt = TRI ? (q0 + BM) / DT_ROWS : p.c / DT_ROWS;
+    const int mask_base = a - p.off - 4 * h;     // sub-tile v: allowed iff 8 (r/4) + r%4 <= mask_base - 32 v
+
+    uint32_t arow[8], tr0[4], tr1[4], gl[4];
+    dt_row_addrs(arow, n, h);
+    dt_tr_addrs(tr0, tr1, lane);
+    dt_load_offsets(gl, lane, wave);
+    char* const kbuf = lds;
+    char* const vbuf = lds + 2 * DT_BYTES;
+    dt_load(K, kbuf, gl, wave);
+    dt_load(V, vbuf, gl, wave);
+    dt_load(K + DT_BYTES, kbuf + DT_BYTES, gl, wave);       // n_kt >= 2 always
+    dt_load(V + DT_BYTES, vbuf + DT_BYTES, gl, wave);
 
     bf16x8 qf[8], gf[8];
     load_b_frags(qf, Q + (int64_t)a * D, h);
@@ -71,61 +136,75 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
     const float kappa = p.scale * LOG2E;
     const float lse2 = p.lse[sbase + a] * LOG2E;
     const float delta = p.delta[sbase + a];
-
     f32x16 acc[4];
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[mb][r] = 0.f;
 
-    u32x4 rk[4], rvr[4];
-    uint32_t rq[16];
-    load_rows(rk, K, tid);
-    load_quads(rq, K, tid);
-    load_rows(rvr, V, tid);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
 
-    for (int kt = 0; kt < n_kt; ++kt) {
-        store_rows(rk, lds + DQ_K, tid);
-        store_transposed(rq, lds + DQ_KT, tid);
-        store_rows(rvr, lds + DQ_V, tid);
-        __syncthreads();
-        {   // prefetch the next tile (the last iteration re-reads its own)
-            const int64_t nxt = (int64_t)min(kt + 1, n_kt - 1) * BN * D;
-            load_rows(rk, K + nxt, tid);
-            load_quads(rq, K + nxt, tid);
-            load_rows(rvr, V + nxt, tid);
+    f32x16 s_a, s_b, dp_a, dp_b;
+    {   // prologue: S(0), dP(0)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s_a[r] = dp_a[r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            s_a = mfma(dt_read_row(kbuf, arow[ks]), qf[ks], s_a);
+            dp_a = mfma(dt_read_row(vbuf, arow[ks]), gf[ks], dp_a);
         }
-        if (kt <= wave_last) {
-            const bool need_mask = tri && kt * BN + BN - 1 > a_lo - off;
-            const int lim = a - off - kt * BN - 4 * h;     // allowed iff 32 kb + 8 (r/4) + r%4 <= lim
-            bf16x8 dsb[4];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-                f32x16 s, dp;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) s[r] = dp[r] = 0.f;
-#pragma unroll
-                for (int ks = 0; ks < 8; ++ks) {
-                    s = mfma(read_a_rows(lds + DQ_K, kb * 32 + n, ks, h), qf[ks], s);
-                    dp = mfma(read_a_rows(lds + DQ_V, kb * 32 + n, ks, h), gf[ks], dp);
-                }
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    float pr = __builtin_amdgcn_exp2f(fmaf(s[r], kappa, -lse2));
-                    if (need_mask && 32 * kb + 8 * (r / 4) + (r % 4) > lim) pr = 0.f;
-                    s[r] = pr * (dp[r] - delta);
-                }
-                dsb[2 * kb] = pack8(s, 0);
-                dsb[2 * kb + 1] = pack8(s, 8);
+    }
+
+    // Trip t = iterations 2t (scores in *_a) and 2t+1 (scores in *_b); PAR = t & 1 selects
+    // the buffers of tile t at compile time.
+    auto trip = [&](auto last_c, auto mask_c, auto par_c, int t) {
+        constexpr bool LAST = decltype(last_c)::value, MASK = decltype(mask_c)::value;
+        constexpr int PAR = decltype(par_c)::value;
+        const char* k_cur = kbuf + PAR * DT_BYTES;
+        const char* v_cur = vbuf + PAR * DT_BYTES;
+        const char* k_nxt = kbuf + (PAR ^ 1) * DT_BYTES;
+        const char* v_nxt = vbuf + (PAR ^ 1) * DT_BYTES;
+        dq_step<true, MASK>(s_a, dp_a, s_b, dp_b, acc, qf, gf, kappa, lse2, delta, arow, tr0, tr1,
+                            k_cur + DT_BYTES / 2, v_cur + DT_BYTES / 2, k_cur, mask_base - 64 * t);
+        if (!LAST) {
+            __builtin_amdgcn_s_waitcnt(0);      // tile t+1, requested one iteration ago, has landed
+            __syncthreads();
+        }
+        dq_step<!LAST, MASK>(s_b, dp_b, s_a, dp_a, acc, qf, gf, kappa, lse2, delta, arow, tr0, tr1,
+                             k_nxt, v_nxt, k_cur + DT_BYTES / 2, mask_base - 64 * t - 32);
+        if (!LAST) {
+            __syncthreads();                    // every wavefront is done with tile t
+            if (t + 2 < n_kt) {
+                dt_load(K + (int64_t)(t + 2) * DT_BYTES, kbuf + PAR * DT_BYTES, gl, wave);
+                dt_load(V + (int64_t)(t + 2) * DT_BYTES, vbuf + PAR * DT_BYTES, gl, wave);
             }
-            // dQ^T += K^T dS^T
-#pragma unroll
-            for (int g = 0; g < 4; ++g)
-#pragma unroll
-                for (int mb = 0; mb < 4; ++mb)
-                    acc[mb] = mfma(read_a_trn(lds + DQ_KT, 32 * mb + n, g, h), dsb[g], acc[mb]);
         }
-        __syncthreads();
+    };
+    using T = std::true_type;
+    using F = std::false_type;
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    int t = 0;
+    if (TRI) {
+        // trips 0 .. n_kt - 3 without the element mask, then two masked trips (n_kt is even)
+        for (; t + 2 < n_kt; t += 2) {
+            trip(F{}, F{}, P0{}, t);
+            trip(F{}, F{}, P1{}, t + 1);
+        }
+        trip(F{}, T{}, P0{}, t);
+        trip(T{}, T{}, P1{}, t + 1);
+    } else {
+        for (; t + 2 < n_kt; t += 2) {
+            trip(F{}, F{}, P0{}, t);
+            trip(F{}, F{}, P1{}, t + 1);
+        }
+        if (t + 1 < n_kt) {
+            trip(F{}, F{}, P0{}, t);
+            trip(T{}, F{}, P1{}, t + 1);
+        } else {
+            trip(T{}, F{}, P0{}, t);
+        }
     }
 
 #pragma unroll
@@ -141,120 +220,208 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
 }
 
 // ------------------------------------------------------------- dK/dV kernel
-constexpr int KV_Q = 0;                            // Q rows
-constexpr int KV_QT = ROW_TILE;                    // Q transposed
-constexpr int KV_G = ROW_TILE + TRN_TILE;          // dO rows
-constexpr int KV_GT = 2 * ROW_TILE + TRN_TILE;     // dO transposed
-constexpr int KV_ELEMS = 2 * ROW_TILE + 2 * TRN_TILE;
+// A workgroup owns 128 key rows (K and V rows in registers as B operands, dK^T and
+// dV^T accumulators in registers: one wavefront per SIMD with the large register
+// budget).  Q and dO tiles (64 query rows) stream global -> LDS directly into swizzled
+// tiles, two buffers each; LSE * log2(e) and delta of the tile's rows are staged
+// beside them.  Iteration u over 32-query sub-tiles issues, interleaved slice by slice,
+//     S(u+1) = Q(u+1) K^T, dP(u+1) = dO(u+1) V^T   (16 MFMA)
+//     P(u) = exp2(S(u) kappa - LSE), dS(u) = P (dP(u) - delta)   (VALU)
+// and then dV^T += dO(u)^T P(u), dK^T += Q(u)^T dS(u) (16 MFMA, the transposed
+// operands through the transposing LDS read).
+constexpr int KV_TILES_BYTES = 4 * DT_BYTES;                 // Q0, Q1, dO0, dO1
+constexpr int KV_STAT_FLOATS = 2 * 2 * DT_ROWS;              // [buffer][lse2 | delta][64]
 
+template <bool NEXT, bool MASK>
+__device__ inline void dkdv_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, f32x16& dp_next,
+                                 f32x16 (&acck)[4], f32x16 (&accv)[4], const bf16x8 (&kf)[8],
+                                 const bf16x8 (&vf)[8], float kappa, const uint32_t (&arow)[8],
+                                 const uint32_t (&tr0)[4], const uint32_t (&tr1)[4], const char* q_next,
+                                 const char* g_next, const char* q_cur, const char* g_cur,
+                                 const float* stat_cur, int h, int mask_lim) {
+    // LSE * log2(e) and delta of this lane's 16 query rows 8 (r/4) + 4h + r%4
+    float lv[16], dv[16];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const float4 l4 = *reinterpret_cast<const float4*>(stat_cur + 8 * g + 4 * h);
+        const float4 d4 = *reinterpret_cast<const float4*>(stat_cur + DT_ROWS + 8 * g + 4 * h);
+        lv[4 * g + 0] = l4.x; lv[4 * g + 1] = l4.y; lv[4 * g + 2] = l4.z; lv[4 * g + 3] = l4.w;
+        dv[4 * g + 0] = d4.x; dv[4 * g + 1] = d4.y; dv[4 * g + 2] = d4.z; dv[4 * g + 3] = d4.w;
+    }
+    bf16x8 qa[8], ga[8], qt[8], gt[8], pb[2], dsb[2];
+    auto fetch = [&](int i) {
+        if (NEXT) {
+            qa[i] = dt_read_row(q_next, arow[i]);
+            ga[i] = dt_read_row(g_next, arow[i]);
+        }
+    };
+    auto fetch_t = [&](int i) {
+        gt[i] = dt_read_tr(g_cur + (i / 4) * 16 * 256, tr0[i % 4], tr1[i % 4]);
+        qt[i] = dt_read_tr(q_cur + (i / 4) * 16 * 256, tr0[i % 4], tr1[i % 4]);
+    };
+    constexpr int AHEAD = 3;
+#pragma unroll
+    for (int i = 0; i < AHEAD; ++i) fetch(i);
+    if (NEXT) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s_next[r] = dp_next[r] = 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        __builtin_amdgcn_sched_barrier(0);          // slices stay in program order
+        if (i + AHEAD < 8) fetch(i + AHEAD);
+        if (i >= 3) fetch_t(i - 3);                 // transposed operands 0..4 ahead of their use
+        if (NEXT) {
+            s_next = mfma(qa[i], kf[i], s_next);
+            dp_next = mfma(ga[i], vf[i], dp_next);
+        }
+#pragma unroll
+        for (int r = 2 * i; r < 2 * i + 2; ++r) {
+            float pr = __builtin_amdgcn_exp2f(fmaf(s_cur[r], kappa, -lv[r]));
+            if (MASK && 8 * (r / 4) + (r % 4) < mask_lim) pr = 0.f;
+            pb[r / 8][r % 8] = (__bf16)pr;
+            dsb[r / 8][r % 8] = (__bf16)(pr * (dp_cur[r] - dv[r]));
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        if (i + 5 < 8) fetch_t(i + 5);
+        accv[i % 4] = mfma(gt[i], pb[i / 4], accv[i % 4]);
+        acck[i % 4] = mfma(qt[i], dsb[i / 4], acck[i % 4]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+template <bool TRI>
 __global__ void __launch_bounds__(256, 1)
 bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
-    __shared__ __attribute__((aligned(16))) __bf16 lds[KV_ELEMS];
-    __shared__ __attribute__((aligned(16))) float stat[2][BN];     // LSE * log2(e), delta of the query tile
+    __shared__ __attribute__((aligned(1024))) char lds[KV_TILES_BYTES];
+    __shared__ __attribute__((aligned(16))) float stat[KV_STAT_FLOATS];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, h = lane >> 5;
-    const bool tri = p.kind == MASK_TRI;
     int ktile, bh;                                // triangular steps: low key tiles see most queries: first
     decode_block((int)blockIdx.x, n_tiles, p.B * p.H, ktile, bh);
     const int b = bh / p.H, hd = bh - b * p.H;
     const int64_t base = b * p.stride_b + hd * p.stride_h;
     const int64_t sbase = b * p.stat_stride_b + hd * p.stat_stride_h;
-    const __bf16* Q = (const __bf16*)p.q + base;
+    const char* Q = (const char*)((const __bf16*)p.q + base);
+    const char* G = (const char*)((const __bf16*)p.dout + base);
     const __bf16* K = (const __bf16*)p.k + base;
     const __bf16* V = (const __bf16*)p.v + base;
-    const __bf16* G = (const __bf16*)p.dout + base;
     const float* LSE = p.lse + sbase;
     const float* DEL = p.delta + sbase;
     float* DK = p.dk + base;
     float* DV = p.dv + base;
 
-    const int k0 = ktile * BM, b_lo = k0 + 32 * wave, key = b_lo + n, off = p.off;
-    const int n_qt = p.c / BN;
-    // query tiles holding at least one allowed pair: query a >= key + off
-    const int qt_first = tri ? min(n_qt, (k0 + off) / BN) : 0;
-    const int wave_first = tri ? (b_lo + off) / BN : 0;     // tiles before it are empty for this wavefront
+    const int k0 = ktile * BM, key = k0 + 32 * wave + n;
+    const int n_qt = p.c / DT_ROWS;
+    // query tiles holding at least one allowed pair (query a >= key + off): from tile k0 / 64
+    // on; only its first four 32-query sub-tiles can cross the diagonal for some wavefront
+    const int t_first = TRI ? k0 / DT_ROWS : 0;
+    // sub-tile u: register r (query 32 u + 8 (r/4) + 4h + r%4) is allowed iff
+    // 8 (r/4) + r%4 >= mask_base - 32 u
+    const int mask_base = key + p.off - 4 * h;
+
+    uint32_t arow[8], tr0[4], tr1[4], gl[4];
+    dt_row_addrs(arow, n, h);
+    dt_tr_addrs(tr0, tr1, lane);
+    dt_load_offsets(gl, lane, wave);
+    char* const qbuf = lds;
+    char* const gbuf = lds + 2 * DT_BYTES;
+    const bool two = t_first + 1 < n_qt;
+    dt_load(Q + (int64_t)t_first * DT_BYTES, qbuf + (t_first & 1) * DT_BYTES, gl, wave);
+    dt_load(G + (int64_t)t_first * DT_BYTES, gbuf + (t_first & 1) * DT_BYTES, gl, wave);
+    if (two) {
+        dt_load(Q + (int64_t)(t_first + 1) * DT_BYTES, qbuf + ((t_first + 1) & 1) * DT_BYTES, gl, wave);
+        dt_load(G + (int64_t)(t_first + 1) * DT_BYTES, gbuf + ((t_first + 1) & 1) * DT_BYTES, gl, wave);
+    }
+    // statistics of query tile t -> stat[(t & 1)][0 | 1][64]: threads 0..63 LSE * log2(e), 64..127 delta
+    auto stat_fetch = [&](int t) -> float {
+        if (tid < DT_ROWS) return LSE[t * DT_ROWS + tid] * LOG2E;
+        if (tid < 2 * DT_ROWS) return DEL[t * DT_ROWS + tid - DT_ROWS];
+        return 0.f;
+    };
+    auto stat_store = [&](int t, float x) {
+        if (tid < 2 * DT_ROWS) stat[(t & 1) * 2 * DT_ROWS + tid] = x;
+    };
+    stat_store(t_first, stat_fetch(t_first));
+    if (two) stat_store(t_first + 1, stat_fetch(t_first + 1));
 
     bf16x8 kf[8], vf[8];
     load_b_frags(kf, K + (int64_t)key * D, h);
     load_b_frags(vf, V + (int64_t)key * D, h);
     const float kappa = p.scale * LOG2E;
-
     f32x16 acck[4], accv[4];
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acck[mb][r] = accv[mb][r] = 0.f;
 
-    if (qt_first < n_qt) {
-        u32x4 rqr[4], rgr[4];
-        uint32_t rqq[16], rgq[16];
-        float rstat = 0.f;
-        auto prefetch = [&](int qt) {
-            const int64_t o = (int64_t)qt * BN * D;
-            load_rows(rqr, Q + o, tid);
-            load_quads(rqq, Q + o, tid);
-            load_rows(rgr, G + o, tid);
-            load_quads(rgq, G + o, tid);
-            if (tid < BN) rstat = LSE[qt * BN + tid] * LOG2E;
-            else if (tid < 2 * BN) rstat = DEL[qt * BN + tid - BN];
-        };
-        prefetch(qt_first);
-        for (int qt = qt_first; qt < n_qt; ++qt) {
-            store_rows(rqr, lds + KV_Q, tid);
-            store_transposed(rqq, lds + KV_QT, tid);
-            store_rows(rgr, lds + KV_G, tid);
-            store_transposed(rgq, lds + KV_GT, tid);
-            if (tid < 2 * BN) stat[tid >> 6][tid & 63] = rstat;
-            __syncthreads();
-            prefetch(min(qt + 1, n_qt - 1));
-            if (qt >= wave_first) {
-                const int a0 = qt * BN;
-                // allowed iff key <= a - off; a = a0 + 32 qb + 8 (r/4) + 4h + r%4
-                const bool need_mask = tri && a0 < b_lo + 31 + off;
-                const int lim = key + off - a0 - 4 * h;     // allowed iff 32 qb + 8 (r/4) + r%4 >= lim
-                bf16x8 pb[4], dsb[4];
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+
+    f32x16 s_a, s_b, dp_a, dp_b;
+    {   // prologue: S, dP of the first sub-tile
+        const char* q0p = qbuf + (t_first & 1) * DT_BYTES;
+        const char* g0p = gbuf + (t_first & 1) * DT_BYTES;
 #pragma unroll
-                for (int qb = 0; qb < 2; ++qb) {
-                    f32x16 s, dp;
+        for (int r = 0; r < 16; ++r) s_a[r] = dp_a[r] = 0.f;
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) s[r] = dp[r] = 0.f;
-#pragma unroll
-                    for (int ks = 0; ks < 8; ++ks) {
-                        s = mfma(read_a_rows(lds + KV_Q, qb * 32 + n, ks, h), kf[ks], s);
-                        dp = mfma(read_a_rows(lds + KV_G, qb * 32 + n, ks, h), vf[ks], dp);
-                    }
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const float4 l4 = *reinterpret_cast<const float4*>(&stat[0][32 * qb + 8 * g + 4 * h]);
-                        const float4 d4 = *reinterpret_cast<const float4*>(&stat[1][32 * qb + 8 * g + 4 * h]);
-                        const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
-                        const float dv[4] = {d4.x, d4.y, d4.z, d4.w};
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const int r = 4 * g + e;
-                            float pr = __builtin_amdgcn_exp2f(fmaf(s[r], kappa, -lv[e]));
-                            if (need_mask && 32 * qb + 8 * g + e < lim) pr = 0.f;
-                            s[r] = pr;
-                            dp[r] = pr * (dp[r] - dv[e]);
-                        }
-                    }
-                    pb[2 * qb] = pack8(s, 0);
-                    pb[2 * qb + 1] = pack8(s, 8);
-                    dsb[2 * qb] = pack8(dp, 0);
-                    dsb[2 * qb + 1] = pack8(dp, 8);
-                }
-                // dV^T += dO^T P ; dK^T += Q^T dS
-#pragma unroll
-                for (int g = 0; g < 4; ++g)
-#pragma unroll
-                    for (int mb = 0; mb < 4; ++mb) {
-                        accv[mb] = mfma(read_a_trn(lds + KV_GT, 32 * mb + n, g, h), pb[g], accv[mb]);
-                        acck[mb] = mfma(read_a_trn(lds + KV_QT, 32 * mb + n, g, h), dsb[g], acck[mb]);
-                    }
-            }
-            __syncthreads();
+        for (int ks = 0; ks < 8; ++ks) {
+            s_a = mfma(dt_read_row(q0p, arow[ks]), kf[ks], s_a);
+            dp_a = mfma(dt_read_row(g0p, arow[ks]), vf[ks], dp_a);
         }
     }
+
+    float rstat = 0.f;          // statistics of the tile after next, in flight
+    // Trip t = iterations 2t (scores in *_a) and 2t+1 (scores in *_b) on query tile t.
+    auto trip = [&](auto mask_c, auto par_c, int t) {
+        constexpr bool MASK = decltype(mask_c)::value;
+        constexpr int PAR = decltype(par_c)::value;
+        const bool last = t + 1 == n_qt;
+        const char* q_cur = qbuf + PAR * DT_BYTES;
+        const char* g_cur = gbuf + PAR * DT_BYTES;
+        const char* q_nxt = qbuf + (PAR ^ 1) * DT_BYTES;
+        const char* g_nxt = gbuf + (PAR ^ 1) * DT_BYTES;
+        const float* st = stat + PAR * 2 * DT_ROWS;
+        dkdv_step<true, MASK>(s_a, dp_a, s_b, dp_b, acck, accv, kf, vf, kappa, arow, tr0, tr1,
+                              q_cur + DT_BYTES / 2, g_cur + DT_BYTES / 2, q_cur, g_cur, st, h,
+                              mask_base - 64 * t);
+        if (!last) {
+            if (t > t_first) stat_store(t + 1, rstat);     // fetched at the end of trip t-1
+            __builtin_amdgcn_s_waitcnt(0);       // tile t+1, requested one iteration ago, has landed
+            __syncthreads();
+            dkdv_step<true, MASK>(s_b, dp_b, s_a, dp_a, acck, accv, kf, vf, kappa, arow, tr0, tr1, q_nxt,
+                                  g_nxt, q_cur + DT_BYTES / 2, g_cur + DT_BYTES / 2, st + 32, h,
+                                  mask_base - 64 * t - 32);
+            __syncthreads();                     // every wavefront is done with tile t
+            if (t + 2 < n_qt) {
+                dt_load(Q + (int64_t)(t + 2) * DT_BYTES, qbuf + PAR * DT_BYTES, gl, wave);
+                dt_load(G + (int64_t)(t + 2) * DT_BYTES, gbuf + PAR * DT_BYTES, gl, wave);
+                rstat = stat_fetch(t + 2);
+            }
+        } else {
+            dkdv_step<false, MASK>(s_b, dp_b, s_a, dp_a, acck, accv, kf, vf, kappa, arow, tr0, tr1, q_nxt,
+                                   g_nxt, q_cur + DT_BYTES / 2, g_cur + DT_BYTES / 2, st + 32, h,
+                                   mask_base - 64 * t - 32);
+        }
+    };
+    using T = std::true_type;
+    using F = std::false_type;
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    int t = t_first;                             // even for triangular steps (k0 is a multiple of 128)
+    if (TRI) {                                   // the first two trips carry the element mask
+        trip(T{}, P0{}, t);
+        if (t + 1 < n_qt) trip(T{}, P1{}, t + 1);
+        t += 2;
+    }
+    for (; t + 1 < n_qt; t += 2) {
+        trip(F{}, P0{}, t);
+        trip(F{}, P1{}, t + 1);
+    }
+    if (t < n_qt) trip(F{}, P0{}, t);
 
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb)
@@ -280,10 +447,16 @@ bool bwd_mfma_supported(const StepArgs& a, int dtype) {
 
 hipError_t launch_bwd_mfma(const StepArgs& a, hipStream_t st) {
     const int n_tiles = a.c / BM;
-    hipLaunchKernelGGL(bwd_dq_mfma_kernel, dim3(n_tiles * a.B * a.H), dim3(256), 0, st, a, n_tiles);
+    if (a.kind == MASK_TRI)
+        hipLaunchKernelGGL(bwd_dq_mfma_kernel<true>, dim3(n_tiles * a.B * a.H), dim3(256), 0, st, a, n_tiles);
+    else
+        hipLaunchKernelGGL(bwd_dq_mfma_kernel<false>, dim3(n_tiles * a.B * a.H), dim3(256), 0, st, a, n_tiles);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(bwd_dkdv_mfma_kernel, dim3(n_tiles * a.B * a.H), dim3(256), 0, st, a, n_tiles);
+    if (a.kind == MASK_TRI)
+        hipLaunchKernelGGL(bwd_dkdv_mfma_kernel<true>, dim3(n_tiles * a.B * a.H), dim3(256), 0, st, a, n_tiles);
+    else
+        hipLaunchKernelGGL(bwd_dkdv_mfma_kernel<false>, dim3(n_tiles * a.B * a.H), dim3(256), 0, st, a, n_tiles);
     return hipGetLastError();
 }
 

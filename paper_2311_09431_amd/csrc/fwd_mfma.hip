@@ -64,17 +64,7 @@ constexpr float RESCALE_LOG2 = 8.f;
 
 typedef __attribute__((address_space(3))) char lds_char;
 typedef __attribute__((address_space(1))) const char global_char;
-typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-
-// max / sum over the two half-waves (lanes n and n + 32 hold the same query)
-__device__ inline float half_wave_max(float x) {
-    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-__device__ inline float half_wave_sum(float x) {
-    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
+typedef lds_s16x4_t lds_s16x4;
 
 // One tile (64 rows) of K or V: 16 KiB = 16 wavefront loads of 1 KiB, 4 per wavefront.
 // g[j]: this lane's byte offset into the tile for its j-th load.

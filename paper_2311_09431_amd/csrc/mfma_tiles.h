@@ -80,38 +80,85 @@ __device__ inline bf16x8 read_a_trn(const __bf16* lds_tile, int col, int g, int 
     return *reinterpret_cast<const bf16x8*>(lds_tile + col * TS + 16 * g + 8 * h);
 }
 
-// Transposing A-operand reads (ds_read_b64_tr_b16) from a ROW-MAJOR tile whose
-// rows are the contraction index (e.g. V[key][d] for O^T += V^T P^T), row stride
-// XS elements.  Within each block of 16 lanes the instruction hands lane i the
-// i-th 16-bit element of what lanes 4e + i/4 (e = 0..3) point at, so lane j of a
-// block points at row j/4, columns 4 (j%4) .. +3 of a 4 x 16 patch and every
+// ---------------------------------------------------------------------------
+// Swizzled tiles filled by direct global -> LDS loads.
+//
+// A tile is 64 rows x 256 bytes (128 bf16) with NO padding: global_load_lds
+// writes the 64 lanes' 16-byte pieces contiguously (1 KiB per wavefront
+// instruction, 4 rows), so a 16 KiB tile takes 16 instructions, 4 per
+// wavefront.  Bank conflicts are avoided by storing the 16-byte chunk c of row
+// r at chunk position c ^ f(r), f(r) = ((r & 3) << 2) | ((r >> 2) & 3):
+//  * 16-byte A-operand row reads (16 consecutive rows, same logical chunk) hit
+//    16 different chunks, because f is a bijection of r & 15;
+//  * the transposing 8-byte reads (ds_read_b64_tr_b16: 4 consecutive rows x two
+//    neighbouring 32-byte chunk pairs per half-wave) hit 8 different pairs.
+// The swizzle is applied on the global side: the lane that fills chunk position
+// pc of row r fetches logical chunk pc ^ f(r).
+//
+// Transposing read.  Within each block of 16 lanes the instruction hands lane i
+// the i-th 16-bit element of what lanes 4e + i/4 (e = 0..3) point at, so lane j
+// of a block points at row j/4, columns 4 (j%4) .. +3 of a 4 x 16 patch and every
 // lane receives 4 consecutive rows of one column.  Two reads (rows +0 and +8)
-// give the 8 contraction values {0..3, 8..11} + 4h of a group of 16 that match a
-// C/D tile used as B operand.  XS = 128 + 32 keeps both the 16-byte row writes and
-// these 8-byte reads free of bank conflicts (row stride = 16 banks mod 64).
-constexpr int XS = TD + 32;
-constexpr int X_TILE = TR * XS;      // elements
+// give the 8 contraction values {0..3, 8..11} + 4h of a group of 16 rows that
+// match a C/D tile used as B operand.
+constexpr int DT_ROWS = 64;
+constexpr int DT_BYTES = DT_ROWS * 256;          // 16 KiB
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) char lds_char_t;
+typedef __attribute__((address_space(1))) const char global_char_t;
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4_t;
 
-__device__ inline void store_rows_x(const u32x4 (&r)[4], __bf16* __restrict__ lds_tile, int tid) {
-    __bf16* p = lds_tile + (tid >> 4) * XS + (tid & 15) * 8;
+__device__ inline int dt_swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
+
+// byte offsets (within a tile, global side) of the 4 pieces this lane fetches
+__device__ inline void dt_load_offsets(uint32_t (&g)[4], int lane, int wave) {
+    const int lr = lane >> 4, pc = lane & 15;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(p + i * 16 * XS) = r[i];
+    for (int j = 0; j < 4; ++j) {
+        const int r = 16 * wave + 4 * j + lr;
+        g[j] = r * 256 + ((pc ^ dt_swz(r)) << 4);
+    }
 }
-// per-lane element offset of the patch this lane points at (group 0, column block 0)
-__device__ inline int tr_lane_offset(int lane) {
-    const int i = lane & 15;
-    return (4 * (lane >> 5) + (i >> 2)) * XS + 16 * ((lane >> 4) & 1) + 4 * (i & 3);
+__device__ inline void dt_load(const char* __restrict__ gtile, char* lds_tile, const uint32_t (&g)[4], int wave) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        __builtin_amdgcn_global_load_lds((global_char_t*)(gtile + g[j]),
+                                         (lds_char_t*)(lds_tile + (4 * wave + j) * 1024), 16, 0, 0);
 }
-// A operand for column block mb (32 columns) and row group g (16 rows)
-__device__ inline bf16x8 read_a_tr(const __bf16* lds_tile, int lane_off, int g, int mb) {
-    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-    const __bf16* p = lds_tile + lane_off + 16 * g * XS + 32 * mb;
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 8 * XS));
-    const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    return __builtin_bit_cast(bf16x8, both);
+// A-operand row reads: address of row n (within a 32-row half tile), k-step ks, half h
+__device__ inline void dt_row_addrs(uint32_t (&a)[8], int n, int h) {
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) a[ks] = n * 256 + (((2 * ks + h) ^ dt_swz(n)) << 4);
+}
+__device__ inline bf16x8 dt_read_row(const char* lds_half, uint32_t addr) {
+    return *reinterpret_cast<const bf16x8*>(lds_half + addr);
+}
+// Transposing reads: addresses (within a group of 16 rows) for 32-column block mb,
+// first read (rows +0) and second read (rows +8)
+__device__ inline void dt_tr_addrs(uint32_t (&t0)[4], uint32_t (&t1)[4], int lane) {
+    const int i = lane & 15, h = lane >> 5, nh = (lane >> 4) & 1, j4 = i >> 2;
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb) {
+        const int c = 4 * mb + 2 * nh + ((i & 3) >> 1);      // logical 16-byte chunk
+        const int r0 = 4 * h + j4, r1 = r0 + 8;
+        t0[mb] = r0 * 256 + ((c ^ dt_swz(r0)) << 4) + (i & 1) * 8;
+        t1[mb] = r1 * 256 + ((c ^ dt_swz(r1)) << 4) + (i & 1) * 8;
+    }
+}
+__device__ inline bf16x8 dt_read_tr(const char* lds_group, uint32_t a0, uint32_t a1) {
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(lds_group + a0));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(lds_group + a1));
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+// max / sum over the two half-waves (lanes n and n + 32)
+__device__ inline float half_wave_max(float x) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ inline float half_wave_sum(float x) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
 __device__ inline f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
