@@ -102,7 +102,7 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, h = lane >> 5;
     int rank, bh;
-    decode_block((int)blockIdx.x, n_tiles, p.B * p.H, rank, bh);
+    decode_block<true>((int)blockIdx.x, n_tiles, p.B * p.H, rank, bh);
     const int qt = TRI ? n_tiles - 1 - rank : rank;      // heaviest query tiles first
     const int b = bh / p.H, hd = bh - b * p.H;
     const int64_t base = b * p.stride_b + hd * p.stride_h;
@@ -301,7 +301,7 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, h = lane >> 5;
     int ktile, bh;                                // triangular steps: low key tiles see most queries: first
-    decode_block((int)blockIdx.x, n_tiles, p.B * p.H, ktile, bh);
+    decode_block<false>((int)blockIdx.x, n_tiles, p.B * p.H, ktile, bh);
     const int b = bh / p.H, hd = bh - b * p.H;
     const int64_t base = b * p.stride_b + hd * p.stride_h;
     const int64_t sbase = b * p.stat_stride_b + hd * p.stat_stride_h;

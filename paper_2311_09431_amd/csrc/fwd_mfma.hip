@@ -167,7 +167,7 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
 
     const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, h = lane >> 5, wave = tid >> 6;
     int rank, bh;
-    decode_block((int)blockIdx.x, n_qtiles, p.B * p.H, rank, bh);
+    decode_block<true>((int)blockIdx.x, n_qtiles, p.B * p.H, rank, bh);
     const int qt = TRI ? n_qtiles - 1 - rank : rank;      // triangular steps: heaviest query tiles first
     const int b = bh / p.H, hd = bh - b * p.H;
     const int64_t base = b * p.stride_b + hd * p.stride_h;

@@ -165,14 +165,28 @@ __device__ inline f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
-// Workgroup order of a 1-D grid over (tile rank, batch*head).  Heads are taken in
-// groups of 8; inside a group the index runs over heads fastest and tile ranks
-// slowest, so (i) with rank 0 the heaviest tile, every group runs heaviest-first
-// and the last workgroups to start are the lightest, and (ii) as consecutive
-// workgroups go round-robin to the 8 XCDs, all tiles of one head land on one XCD
-// and share its L2 while they stream the same K/V (or Q/dO) rows.
+// Workgroup order of a 1-D grid over (tile rank, batch*head), rank 0 = heaviest tile.
+// Large grids: heads are taken in groups of 8; inside a group the index runs over
+// heads fastest and tile ranks slowest, so (i) every group runs heaviest-first and
+// the last workgroups to start are the lightest, and (ii) as consecutive workgroups
+// go round-robin to the 8 XCDs, all tiles of one head land on one XCD and share its
+// L2 while they stream the same K/V (or Q/dO) rows.
+// Small grids (every workgroup resident at once, at most 2 per CU): plain
+// heaviest-first over all heads; with SNAKE the second 256 workgroups run
+// lightest-first, so that the two workgroups sharing a CU (indices L and L + 256)
+// carry about the same total work.
 constexpr int HEAD_GROUP = 8;
+constexpr int N_CU = 256;
+template <bool SNAKE>
 __device__ inline void decode_block(int linear, int n_tiles, int n_bh, int& rank, int& bh) {
+    const int total = n_tiles * n_bh;
+    if (total <= 2 * N_CU) {
+        int s = linear;
+        if (SNAKE && linear >= N_CU) s = total - 1 - (linear - N_CU);
+        rank = s / n_bh;
+        bh = s - rank * n_bh;
+        return;
+    }
     const int per_group = HEAD_GROUP * n_tiles;
     const int grp = linear / per_group;
     const int within = linear - grp * per_group;
