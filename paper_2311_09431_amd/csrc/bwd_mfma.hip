@@ -239,15 +239,6 @@ __device__ inline void dkdv_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, 
                                  const uint32_t (&tr0)[4], const uint32_t (&tr1)[4], const char* q_next,
                                  const char* g_next, const char* q_cur, const char* g_cur,
                                  const float* stat_cur, int h, int mask_lim) {
-    // LSE * log2(e) and delta of this lane's 16 query rows 8 (r/4) + 4h + r%4
-    float lv[16], dv[16];
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-        const float4 l4 = *reinterpret_cast<const float4*>(stat_cur + 8 * g + 4 * h);
-        const float4 d4 = *reinterpret_cast<const float4*>(stat_cur + DT_ROWS + 8 * g + 4 * h);
-        lv[4 * g + 0] = l4.x; lv[4 * g + 1] = l4.y; lv[4 * g + 2] = l4.z; lv[4 * g + 3] = l4.w;
-        dv[4 * g + 0] = d4.x; dv[4 * g + 1] = d4.y; dv[4 * g + 2] = d4.z; dv[4 * g + 3] = d4.w;
-    }
     bf16x8 qa[8], ga[8], qt[8], gt[8], pb[2], dsb[2];
     auto fetch = [&](int i) {
         if (NEXT) {
@@ -259,9 +250,18 @@ __device__ inline void dkdv_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, 
         gt[i] = dt_read_tr(g_cur + (i / 4) * 16 * 256, tr0[i % 4], tr1[i % 4]);
         qt[i] = dt_read_tr(q_cur + (i / 4) * 16 * 256, tr0[i % 4], tr1[i % 4]);
     };
-    constexpr int AHEAD = 3;
+    // LSE * log2(e) and delta of this lane's query rows 8 (r/4) + 4h + r%4, two per slice
+    float2 lv[8], dv[8];
+    auto fetch_stat = [&](int i) {
+        lv[i] = *reinterpret_cast<const float2*>(stat_cur + 8 * (i / 2) + 4 * h + 2 * (i % 2));
+        dv[i] = *reinterpret_cast<const float2*>(stat_cur + DT_ROWS + 8 * (i / 2) + 4 * h + 2 * (i % 2));
+    };
+    constexpr int AHEAD = 2;
 #pragma unroll
-    for (int i = 0; i < AHEAD; ++i) fetch(i);
+    for (int i = 0; i < AHEAD; ++i) {
+        fetch(i);
+        fetch_stat(i);
+    }
     if (NEXT) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) s_next[r] = dp_next[r] = 0.f;
@@ -269,24 +269,28 @@ __device__ inline void dkdv_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, 
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         __builtin_amdgcn_sched_barrier(0);          // slices stay in program order
-        if (i + AHEAD < 8) fetch(i + AHEAD);
-        if (i >= 3) fetch_t(i - 3);                 // transposed operands 0..4 ahead of their use
+        if (i + AHEAD < 8) {
+            fetch(i + AHEAD);
+            fetch_stat(i + AHEAD);
+        }
+        if (i >= 5) fetch_t(i - 5);                 // transposed operands 0..2 ahead of their use
         if (NEXT) {
             s_next = mfma(qa[i], kf[i], s_next);
             dp_next = mfma(ga[i], vf[i], dp_next);
         }
 #pragma unroll
         for (int r = 2 * i; r < 2 * i + 2; ++r) {
-            float pr = __builtin_amdgcn_exp2f(fmaf(s_cur[r], kappa, -lv[r]));
+            const float lr = (r & 1) ? lv[i].y : lv[i].x, dr = (r & 1) ? dv[i].y : dv[i].x;
+            float pr = __builtin_amdgcn_exp2f(fmaf(s_cur[r], kappa, -lr));
             if (MASK && 8 * (r / 4) + (r % 4) < mask_lim) pr = 0.f;
             pb[r / 8][r % 8] = (__bf16)pr;
-            dsb[r / 8][r % 8] = (__bf16)(pr * (dp_cur[r] - dv[r]));
+            dsb[r / 8][r % 8] = (__bf16)(pr * (dp_cur[r] - dr));
         }
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        if (i + 5 < 8) fetch_t(i + 5);
+        if (i + 3 < 8) fetch_t(i + 3);
         accv[i % 4] = mfma(gt[i], pb[i / 4], accv[i % 4]);
         acck[i % 4] = mfma(qt[i], dsb[i / 4], acck[i % 4]);
         __builtin_amdgcn_sched_barrier(0);
