@@ -174,3 +174,34 @@ def test_one_devices_share_at_786k_forward_and_backward(layout):
         if layout == sa.STRIPED:
             gh = orc.unstripe_permute(gh, N, 0)
         _check_grads(name, gh, w)
+
+
+@pytest.mark.parametrize("layout", [sa.STRIPED, sa.CONTIGUOUS])
+def test_head_count_not_a_multiple_of_the_head_group(layout):
+    # 10 heads x 64 query tiles = 640 workgroups: the large-grid order with a partial last
+    # group of heads; batch 2 exercises the batch stride.  Forward and backward, sampled rows.
+    B, H, S, d, N = 2, 5, 16384, 128, 2
+    c = S // N
+    Q, K, V = inputs.qkv(B, H, S, d, 6, torch.bfloat16, device="cuda")
+    R = sorted(set([0, 1, 127, 128, c - 1, c, S - 1] + np.random.default_rng(6).integers(0, S, 25).tolist()))
+    dO = _sparse_dout(B, H, S, d, R, 66)
+    Qp, Kp, Vp, dOp = _device_order([Q, K, V, dO], N, layout)
+    O = torch.empty(B, H, S, d, dtype=torch.float32, device="cuda")
+    LSE = torch.empty(B, H, S, dtype=torch.float32, device="cuda")
+    shape = sa.shard_shape(Qp, c, LSE)
+    sa.sa_ring_fwd(Qp, Kp, Vp, O, LSE, N, layout, shape)
+    delta = torch.empty_like(LSE)
+    dQ, dK, dV = (torch.empty_like(O) for _ in range(3))
+    sa.sa_ring_bwd(Qp, Kp, Vp, dOp, O, LSE, delta, dQ, dK, dV, N, layout, shape)
+    torch.cuda.synchronize()
+    scale = 1.0 / np.sqrt(d)
+    un = (lambda x: orc.unstripe_permute(x, N, 0)) if layout == sa.STRIPED else (lambda x: x)
+    for b, h in ((0, 0), (1, 4), (1, 2)):
+        f64 = lambda x: x[b, h].to("cpu").to(torch.float64).numpy()
+        Qh, Kh, Vh, Gh = f64(Q), f64(K), f64(V), f64(dO)
+        Ow, Lw = orc.causal_attention_rows(Qh, Kh, Vh, scale, R)
+        assert np.abs(un(O[b, h].cpu().numpy())[R] - Ow).max() <= TOL_O
+        assert np.abs(un(LSE[b, h].cpu().numpy())[R] - Lw).max() <= TOL_LSE
+        want = orc.causal_attention_grad(Qh, Kh, Vh, Gh, scale, rows=R)
+        for name, g, w in zip(("dQ", "dK", "dV"), (dQ, dK, dV), want):
+            _check_grads(name, un(g[b, h].cpu().numpy()), w)
