@@ -220,6 +220,19 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
 }
 
 // ------------------------------------------------------------- dK/dV kernel
+// MFMA whose accumulator is pinned to ordinary VGPRs.  The dK/dV kernel needs more than 256
+// registers, and once a kernel uses AGPRs the compiler places EVERY MFMA result there; the
+// S / dP tiles are consumed by VALU instructions, so they would be copied back register by
+// register.  Results of these are read by VALU code one whole pipeline step later (hundreds
+// of cycles), far beyond the MFMA -> VALU read hazard window the compiler cannot see through
+// the asm; the prologue, where the distance is short, waits explicitly.
+__device__ inline void mfma_vgpr_first(f32x16& acc, bf16x8 a, bf16x8 b) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "v"(b));
+}
+__device__ inline void mfma_vgpr_acc(f32x16& acc, bf16x8 a, bf16x8 b) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+
 // A workgroup owns 128 key rows (K and V rows in registers as B operands, dK^T and
 // dV^T accumulators in registers: one wavefront per SIMD with the large register
 // budget).  Q and dO tiles (64 query rows) stream global -> LDS directly into swizzled
@@ -262,10 +275,6 @@ __device__ inline void dkdv_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, 
         fetch(i);
         fetch_stat(i);
     }
-    if (NEXT) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s_next[r] = dp_next[r] = 0.f;
-    }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         __builtin_amdgcn_sched_barrier(0);          // slices stay in program order
@@ -275,8 +284,13 @@ __device__ inline void dkdv_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, 
         }
         if (i >= 5) fetch_t(i - 5);                 // transposed operands 0..2 ahead of their use
         if (NEXT) {
-            s_next = mfma(qa[i], kf[i], s_next);
-            dp_next = mfma(ga[i], vf[i], dp_next);
+            if (i == 0) {
+                mfma_vgpr_first(s_next, qa[0], kf[0]);
+                mfma_vgpr_first(dp_next, ga[0], vf[0]);
+            } else {
+                mfma_vgpr_acc(s_next, qa[i], kf[i]);
+                mfma_vgpr_acc(dp_next, ga[i], vf[i]);
+            }
         }
 #pragma unroll
         for (int r = 2 * i; r < 2 * i + 2; ++r) {
@@ -369,13 +383,14 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
     {   // prologue: S, dP of the first sub-tile
         const char* q0p = qbuf + (t_first & 1) * DT_BYTES;
         const char* g0p = gbuf + (t_first & 1) * DT_BYTES;
+        mfma_vgpr_first(s_a, dt_read_row(q0p, arow[0]), kf[0]);
+        mfma_vgpr_first(dp_a, dt_read_row(g0p, arow[0]), vf[0]);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s_a[r] = dp_a[r] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            s_a = mfma(dt_read_row(q0p, arow[ks]), kf[ks], s_a);
-            dp_a = mfma(dt_read_row(g0p, arow[ks]), vf[ks], dp_a);
+        for (int ks = 1; ks < 8; ++ks) {
+            mfma_vgpr_acc(s_a, dt_read_row(q0p, arow[ks]), kf[ks]);
+            mfma_vgpr_acc(dp_a, dt_read_row(g0p, arow[ks]), vf[ks]);
         }
+        __builtin_amdgcn_s_sleep(2);      // let the last two MFMAs retire before VALU code reads them
     }
 
     float rstat = 0.f;          // statistics of the tile after next, in flight
