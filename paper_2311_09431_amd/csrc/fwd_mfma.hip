@@ -53,7 +53,8 @@ namespace sa {
 
 namespace {
 
-constexpr int BM = 128;                 // query rows per workgroup
+constexpr int NW = 4;                   // wavefronts per workgroup (8 measured the same at 32768-token shards)
+constexpr int BM = 32 * NW;             // query rows per workgroup
 constexpr int D = TD;                   // head dimension
 constexpr int TILE_ROWS = 64;           // key rows per LDS tile
 constexpr int TILE_BYTES = TILE_ROWS * D * 2;   // 16 KiB
@@ -68,12 +69,13 @@ typedef lds_s16x4_t lds_s16x4;
 
 // One tile (64 rows) of K or V: 16 KiB = 16 wavefront loads of 1 KiB, 4 per wavefront.
 // g[j]: this lane's byte offset into the tile for its j-th load.
+constexpr int LPW = 16 / NW;             // direct loads per wavefront and tile
 __device__ inline void load_tile_direct(const char* __restrict__ gtile, char* lds_tile, const uint32_t (&g)[4],
                                         int wave) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-        __builtin_amdgcn_global_load_lds((global_char*)(gtile + g[j]), (lds_char*)(lds_tile + (4 * wave + j) * 1024),
-                                         16, 0, 0);
+    for (int j = 0; j < LPW; ++j)
+        __builtin_amdgcn_global_load_lds((global_char*)(gtile + g[j]),
+                                         (lds_char*)(lds_tile + (LPW * wave + j) * 1024), 16, 0, 0);
 }
 
 __device__ inline bf16x8 lds_read_b128(const char* lds, uint32_t addr) {
@@ -161,7 +163,7 @@ __device__ inline void step(f32x16& s_cur, f32x16& s_next, bf16x8 (&p_cur)[2], b
 }
 
 template <bool TRI>
-__global__ void __launch_bounds__(256, 2)
+__global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1)
 fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
 
@@ -181,8 +183,8 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     const int a = q0 + 32 * wave + n;         // this lane's query row
     // 64-key tiles holding at least one allowed pair for the workgroup.  Triangular: keys
     // b <= a - off, i.e. tiles 0 .. (q0 + 127) / 64.  All four wavefronts walk all 2 n_kt
-    // sub-tiles (at most three of them are entirely masked for a wavefront); the element
-    // mask is applied on the last four sub-tiles only.
+    // sub-tiles (at most NW - 1 of them are entirely masked for a wavefront); the element
+    // mask is applied on the last NW sub-tiles only.
     const int n_kt = TRI ? (q0 + BM) / TILE_ROWS : p.c / TILE_ROWS;
     // sub-tile v: register r (key 32 v + 8 (r/4) + 4h + r%4) is allowed iff
     // 8 (r/4) + r%4 <= mask_base - 32 v
@@ -203,8 +205,9 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
         const int lr = lane >> 4, pc = lane & 15;      // row within the 4-row group, physical chunk
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            kg[j] = (16 * wave + 4 * j + lr) * 256 + ((pc ^ (4 * j + lr)) << 4);
-            vg[j] = (16 * wave + 4 * j + lr) * 256 + ((pc ^ (lr << 2)) << 4);
+            const int r = 4 * LPW * wave + 4 * j + lr;     // tile row this lane fills with load j
+            kg[j] = r * 256 + ((pc ^ (r & 15)) << 4);
+            vg[j] = r * 256 + ((pc ^ (lr << 2)) << 4);
         }
     }
 
@@ -252,7 +255,7 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     //              requested at barrier t-1, have landed
     //   u = 2t+1: QK(2t+2): K tile t+1, first half     PV(2t): V tile t, first half
     // PAR = t & 1 fixes every LDS offset at compile time.
-    auto trip = [&](auto first_c, auto last_c, auto mask_c, auto par_c, int t) {
+    auto trip = [&](auto first_c, auto last_c, auto mask_c, auto par_c, int t) __attribute__((always_inline)) {
         constexpr bool FIRST = decltype(first_c)::value, LAST = decltype(last_c)::value;
         constexpr bool MASK = decltype(mask_c)::value;
         constexpr int PAR = decltype(par_c)::value;
@@ -273,39 +276,34 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     using F = std::false_type;
     using P0 = std::integral_constant<int, 0>;
     using P1 = std::integral_constant<int, 1>;
-    // masked trips (triangular only): the last two, n_kt - 2 and n_kt - 1
-    const int n_plain = TRI ? n_kt - 2 : n_kt;       // trips 0 .. n_plain - 1 run without the element mask
+    // run trip t with its first / last / parity flags resolved at run time (n_kt >= 2, so a
+    // trip is never both first and last)
+    auto run = [&](auto mask_c, int t) __attribute__((always_inline)) {
+        const bool last = t + 1 == n_kt;
+        if (t & 1) {
+            if (last) trip(F{}, T{}, mask_c, P1{}, t);
+            else trip(F{}, F{}, mask_c, P1{}, t);
+        } else if (t == 0) {
+            trip(T{}, F{}, mask_c, P0{}, t);
+        } else if (last) {
+            trip(F{}, T{}, mask_c, P0{}, t);
+        } else {
+            trip(F{}, F{}, mask_c, P0{}, t);
+        }
+    };
+    // triangular steps: the last BM / 64 trips carry the element mask
+    const int t_mask = TRI ? n_kt - BM / TILE_ROWS : n_kt;
+    const int t_hot = TRI ? t_mask : n_kt - 1;       // plain, neither first nor last: [1, t_hot)
     int t = 0;
-    if (n_plain >= 1) {
-        if (!TRI && n_kt == 1) { /* unreachable: c >= 128 */ }
-        trip(T{}, F{}, F{}, P0{}, 0);
-        t = 1;
-        const int t_end = TRI ? n_plain : n_kt - 1;   // full steps keep the last trip for the LAST variant
-        for (; t + 1 < t_end; t += 2) {
+    if (t_mask > 0) {
+        run(F{}, 0);
+        for (t = 1; t + 1 < t_hot; t += 2) {          // the hot loop: two plain trips per turn
             trip(F{}, F{}, F{}, P1{}, t);
             trip(F{}, F{}, F{}, P0{}, t + 1);
         }
-        if (t < t_end) {
-            trip(F{}, F{}, F{}, P1{}, t);
-            ++t;
-        }
+        for (; t < t_mask; ++t) run(F{}, t);
     }
-    if (TRI) {
-        // t == n_kt - 2 (or 0 when n_kt == 2): two masked trips, the second one is the last
-        if (t == 0) {
-            trip(T{}, F{}, T{}, P0{}, 0);
-            trip(F{}, T{}, T{}, P1{}, 1);
-        } else if (t & 1) {
-            trip(F{}, F{}, T{}, P1{}, t);
-            trip(F{}, T{}, T{}, P0{}, t + 1);
-        } else {
-            trip(F{}, F{}, T{}, P0{}, t);
-            trip(F{}, T{}, T{}, P1{}, t + 1);
-        }
-    } else {
-        if (t & 1) trip(F{}, T{}, F{}, P1{}, t);
-        else trip(F{}, T{}, F{}, P0{}, t);
-    }
+    for (; t < n_kt; ++t) run(T{}, t);
     // final iteration u = 2 n_kt: PV(2 n_kt - 1): V tile n_kt - 1, second half; P in p_b
     {
         const char* v_last = lds + V_BUF0 + ((n_kt - 1) & 1) * TILE_BYTES + TILE_BYTES / 2;
@@ -336,9 +334,9 @@ bool fwd_mfma_supported(const StepArgs& a, int dtype) {
 hipError_t launch_fwd_mfma(const StepArgs& a, hipStream_t st) {
     const int n_qtiles = a.c / BM;
     if (a.kind == MASK_TRI)
-        hipLaunchKernelGGL(fwd_mfma_kernel<true>, dim3(n_qtiles * a.B * a.H), dim3(256), 0, st, a, n_qtiles);
+        hipLaunchKernelGGL(fwd_mfma_kernel<true>, dim3(n_qtiles * a.B * a.H), dim3(64 * NW), 0, st, a, n_qtiles);
     else
-        hipLaunchKernelGGL(fwd_mfma_kernel<false>, dim3(n_qtiles * a.B * a.H), dim3(256), 0, st, a, n_qtiles);
+        hipLaunchKernelGGL(fwd_mfma_kernel<false>, dim3(n_qtiles * a.B * a.H), dim3(64 * NW), 0, st, a, n_qtiles);
     return hipGetLastError();
 }
 
