@@ -108,3 +108,16 @@ def test_binding_refuses_cpu_tensors():
     x = torch.zeros(1, 1, 8, 4)
     with pytest.raises(TypeError):
         sa.sa_stripe_permute(x, x.clone(), 2)
+
+
+def test_header_is_valid_c():
+    # the boundary is a C ABI: the header must compile as plain C
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    src = '#include "striped_attn.h"\nint main(void) { sa_shape s; s.B = 1; return sa_status_str(SA_OK) == (const char*)0 || s.B != 1; }\n'
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-Werror", "-fsyntax-only", "-x", "c", "-I",
+                        os.path.join(ROOT, "include"), "-"], input=src, text=True, capture_output=True)
+    assert r.returncode == 0, r.stderr

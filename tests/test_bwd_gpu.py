@@ -66,3 +66,13 @@ def test_bwd_preprocess_matches_rowsum():
 ])
 def test_mfma_bf16_backward(layout, B, H, S, N):
     _check(B, H, S, 128, N, layout, torch.bfloat16, seed=S + N + 5, use_driver=(N != 2))
+
+
+def test_mfma_backward_is_deterministic():
+    B, H, S, d, N = 1, 2, 1024, 128, 2
+    Q, K, V, dO = (x.cuda() for x in inputs.qkv(B, H, S, d, 32, torch.bfloat16, with_dout=True))
+    a = hp.ring_backward_gpu(Q, K, V, dO, N, sa.STRIPED, use_driver=True)
+    b = hp.ring_backward_gpu(Q, K, V, dO, N, sa.STRIPED, use_driver=True)
+    torch.cuda.synchronize()
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)

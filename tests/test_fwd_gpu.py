@@ -129,3 +129,17 @@ def test_mfma_matches_generic_kernel_on_large_scores():
     # unit-variance q.k with scale 1 gives scores of magnitude ~ sqrt(128): a hard
     # softmax, checked against the oracle with the same tolerances
     _check_ring(1, 1, 512, 128, 2, sa.STRIPED, torch.bfloat16, seed=5, scale=1.0)
+
+
+def test_mfma_forward_is_deterministic_and_honours_the_stream():
+    # no atomics anywhere: two runs give the same bits; and the work goes to the caller's stream
+    B, H, S, d, N = 1, 2, 1024, 128, 4
+    Q, K, V = (x.cuda() for x in inputs.qkv(B, H, S, d, 31, torch.bfloat16))
+    O1, L1 = hp.ring_forward_gpu(Q, K, V, N, sa.STRIPED, use_driver=True)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        O2, L2 = hp.ring_forward_gpu(Q, K, V, N, sa.STRIPED, use_driver=True)
+    side.synchronize()
+    torch.cuda.synchronize()
+    assert torch.equal(O1, O2) and torch.equal(L1, L2)
