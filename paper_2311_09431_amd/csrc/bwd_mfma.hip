@@ -100,7 +100,8 @@ __global__ void __launch_bounds__(256, 2)
 bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
     __shared__ __attribute__((aligned(1024))) char lds[DQ_LDS_BYTES];
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, h = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, h = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform, kept scalar
     int rank, bh;
     decode_block<true>((int)blockIdx.x, n_tiles, p.B * p.H, rank, bh);
     const int qt = TRI ? n_tiles - 1 - rank : rank;      // heaviest query tiles first
@@ -108,8 +109,8 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
     const int64_t base = b * p.stride_b + hd * p.stride_h;
     const int64_t sbase = b * p.stat_stride_b + hd * p.stat_stride_h;
     const __bf16* Q = (const __bf16*)p.q + base;
-    const char* K = (const char*)((const __bf16*)p.k + base);
-    const char* V = (const char*)((const __bf16*)p.v + base);
+    const dt_rsrc Kr = dt_make_rsrc((const __bf16*)p.k + base, p.c);
+    const dt_rsrc Vr = dt_make_rsrc((const __bf16*)p.v + base, p.c);
     const __bf16* G = (const __bf16*)p.dout + base;
     float* DQ = p.dq + base;
 
@@ -125,10 +126,10 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
     dt_load_offsets(gl, lane, wave);
     char* const kbuf = lds;
     char* const vbuf = lds + 2 * DT_BYTES;
-    dt_load(K, kbuf, gl, wave);
-    dt_load(V, vbuf, gl, wave);
-    dt_load(K + DT_BYTES, kbuf + DT_BYTES, gl, wave);       // n_kt >= 2 always
-    dt_load(V + DT_BYTES, vbuf + DT_BYTES, gl, wave);
+    dt_load(Kr, 0, kbuf, gl, wave);
+    dt_load(Vr, 0, vbuf, gl, wave);
+    dt_load(Kr, DT_BYTES, kbuf + DT_BYTES, gl, wave);       // n_kt >= 2 always
+    dt_load(Vr, DT_BYTES, vbuf + DT_BYTES, gl, wave);
 
     bf16x8 qf[8], gf[8];
     load_b_frags(qf, Q + (int64_t)a * D, h);
@@ -176,8 +177,8 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
         if (!LAST) {
             __syncthreads();                    // every wavefront is done with tile t
             if (t + 2 < n_kt) {
-                dt_load(K + (int64_t)(t + 2) * DT_BYTES, kbuf + PAR * DT_BYTES, gl, wave);
-                dt_load(V + (int64_t)(t + 2) * DT_BYTES, vbuf + PAR * DT_BYTES, gl, wave);
+                dt_load(Kr, (t + 2) * DT_BYTES, kbuf + PAR * DT_BYTES, gl, wave);
+                dt_load(Vr, (t + 2) * DT_BYTES, vbuf + PAR * DT_BYTES, gl, wave);
             }
         }
     };
@@ -317,14 +318,15 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
     __shared__ __attribute__((aligned(1024))) char lds[KV_TILES_BYTES];
     __shared__ __attribute__((aligned(16))) float stat[KV_STAT_FLOATS];
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, h = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, h = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform, kept scalar
     int ktile, bh;                                // triangular steps: low key tiles see most queries: first
     decode_block<false>((int)blockIdx.x, n_tiles, p.B * p.H, ktile, bh);
     const int b = bh / p.H, hd = bh - b * p.H;
     const int64_t base = b * p.stride_b + hd * p.stride_h;
     const int64_t sbase = b * p.stat_stride_b + hd * p.stat_stride_h;
-    const char* Q = (const char*)((const __bf16*)p.q + base);
-    const char* G = (const char*)((const __bf16*)p.dout + base);
+    const dt_rsrc Qr = dt_make_rsrc((const __bf16*)p.q + base, p.c);
+    const dt_rsrc Gr = dt_make_rsrc((const __bf16*)p.dout + base, p.c);
     const __bf16* K = (const __bf16*)p.k + base;
     const __bf16* V = (const __bf16*)p.v + base;
     const float* LSE = p.lse + sbase;
@@ -348,11 +350,11 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
     char* const qbuf = lds;
     char* const gbuf = lds + 2 * DT_BYTES;
     const bool two = t_first + 1 < n_qt;
-    dt_load(Q + (int64_t)t_first * DT_BYTES, qbuf + (t_first & 1) * DT_BYTES, gl, wave);
-    dt_load(G + (int64_t)t_first * DT_BYTES, gbuf + (t_first & 1) * DT_BYTES, gl, wave);
+    dt_load(Qr, t_first * DT_BYTES, qbuf + (t_first & 1) * DT_BYTES, gl, wave);
+    dt_load(Gr, t_first * DT_BYTES, gbuf + (t_first & 1) * DT_BYTES, gl, wave);
     if (two) {
-        dt_load(Q + (int64_t)(t_first + 1) * DT_BYTES, qbuf + ((t_first + 1) & 1) * DT_BYTES, gl, wave);
-        dt_load(G + (int64_t)(t_first + 1) * DT_BYTES, gbuf + ((t_first + 1) & 1) * DT_BYTES, gl, wave);
+        dt_load(Qr, (t_first + 1) * DT_BYTES, qbuf + ((t_first + 1) & 1) * DT_BYTES, gl, wave);
+        dt_load(Gr, (t_first + 1) * DT_BYTES, gbuf + ((t_first + 1) & 1) * DT_BYTES, gl, wave);
     }
     // statistics of query tile t -> stat[(t & 1)][0 | 1][64]: threads 0..63 LSE * log2(e), 64..127 delta
     auto stat_fetch = [&](int t) -> float {
@@ -416,8 +418,8 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
                                   mask_base - 64 * t - 32);
             __syncthreads();                     // every wavefront is done with tile t
             if (t + 2 < n_qt) {
-                dt_load(Q + (int64_t)(t + 2) * DT_BYTES, qbuf + PAR * DT_BYTES, gl, wave);
-                dt_load(G + (int64_t)(t + 2) * DT_BYTES, gbuf + PAR * DT_BYTES, gl, wave);
+                dt_load(Qr, (t + 2) * DT_BYTES, qbuf + PAR * DT_BYTES, gl, wave);
+                dt_load(Gr, (t + 2) * DT_BYTES, gbuf + PAR * DT_BYTES, gl, wave);
                 rstat = stat_fetch(t + 2);
             }
         } else {

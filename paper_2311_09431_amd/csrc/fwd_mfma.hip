@@ -70,12 +70,12 @@ typedef lds_s16x4_t lds_s16x4;
 // One tile (64 rows) of K or V: 16 KiB = 16 wavefront loads of 1 KiB, 4 per wavefront.
 // g[j]: this lane's byte offset into the tile for its j-th load.
 constexpr int LPW = 16 / NW;             // direct loads per wavefront and tile
-__device__ inline void load_tile_direct(const char* __restrict__ gtile, char* lds_tile, const uint32_t (&g)[4],
+__device__ inline void load_tile_direct(dt_rsrc matrix, int tile_byte_offset, char* lds_tile, const uint32_t (&g)[4],
                                         int wave) {
 #pragma unroll
     for (int j = 0; j < LPW; ++j)
-        __builtin_amdgcn_global_load_lds((global_char*)(gtile + g[j]),
-                                         (lds_char*)(lds_tile + (LPW * wave + j) * 1024), 16, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(matrix, (lds_char*)(lds_tile + (LPW * wave + j) * 1024), 16,
+                                                 (int)g[j], tile_byte_offset, 0, 0);
 }
 
 __device__ inline bf16x8 lds_read_b128(const char* lds, uint32_t addr) {
@@ -167,15 +167,16 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1)
 fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
 
-    const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, h = lane >> 5, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, h = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform, kept scalar
     int rank, bh;
     decode_block<true>((int)blockIdx.x, n_qtiles, p.B * p.H, rank, bh);
     const int qt = TRI ? n_qtiles - 1 - rank : rank;      // triangular steps: heaviest query tiles first
     const int b = bh / p.H, hd = bh - b * p.H;
     const int64_t base = b * p.stride_b + hd * p.stride_h;
     const __bf16* Q = (const __bf16*)p.q + base;
-    const char* K = (const char*)((const __bf16*)p.k + base);
-    const char* V = (const char*)((const __bf16*)p.v + base);
+    const dt_rsrc K = dt_make_rsrc((const __bf16*)p.k + base, p.c);
+    const dt_rsrc V = dt_make_rsrc((const __bf16*)p.v + base, p.c);
     float* O = p.o + base;
     float* L = p.lse + b * p.stat_stride_b + hd * p.stat_stride_h;
 
@@ -212,9 +213,9 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     }
 
     // first tiles on their way while the running state is loaded
-    load_tile_direct(K, lds + K_BUF0, kg, wave);
-    load_tile_direct(V, lds + V_BUF0, vg, wave);
-    load_tile_direct(K + TILE_BYTES, lds + K_BUF0 + TILE_BYTES, kg, wave);     // n_kt >= 2 always
+    load_tile_direct(K, 0, lds + K_BUF0, kg, wave);
+    load_tile_direct(V, 0, lds + V_BUF0, vg, wave);
+    load_tile_direct(K, TILE_BYTES, lds + K_BUF0 + TILE_BYTES, kg, wave);     // n_kt >= 2 always
 
     bf16x8 qf[8];
     load_b_frags(qf, Q + (int64_t)a * D, h);
@@ -267,8 +268,8 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
                                        k_cur + TILE_BYTES / 2, v_prv + TILE_BYTES / 2, mask_base - 64 * t);
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-        if (t + 2 < n_kt) load_tile_direct(K + (int64_t)(t + 2) * TILE_BYTES, lds + K_BUF0 + PAR * TILE_BYTES, kg, wave);
-        if (t + 1 < n_kt) load_tile_direct(V + (int64_t)(t + 1) * TILE_BYTES, lds + V_BUF0 + (PAR ^ 1) * TILE_BYTES, vg, wave);
+        if (t + 2 < n_kt) load_tile_direct(K, (t + 2) * TILE_BYTES, lds + K_BUF0 + PAR * TILE_BYTES, kg, wave);
+        if (t + 1 < n_kt) load_tile_direct(V, (t + 1) * TILE_BYTES, lds + V_BUF0 + (PAR ^ 1) * TILE_BYTES, vg, wave);
         step<!LAST, true, true, MASK>(s_b, s_a, p_b, p_a, oacc, qf, m, l, kappa, kaddr, vaddr, k_nxt, v_cur,
                                       mask_base - 64 * t - 32);
     };

@@ -120,11 +120,20 @@ __device__ inline void dt_load_offsets(uint32_t (&g)[4], int lane, int wave) {
         g[j] = r * 256 + ((pc ^ dt_swz(r)) << 4);
     }
 }
-__device__ inline void dt_load(const char* __restrict__ gtile, char* lds_tile, const uint32_t (&g)[4], int wave) {
+// The loads go through a buffer descriptor held in scalar registers: the tile's byte
+// offset within the (batch, head) matrix is a scalar operand and the lane offset a 32-bit
+// vector operand, so a load costs no address arithmetic at all.  The descriptor's range is
+// the c rows of the matrix.
+typedef __amdgpu_buffer_rsrc_t dt_rsrc;
+__device__ inline dt_rsrc dt_make_rsrc(const void* matrix, int rows) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(matrix), 0, rows * (TD * 2), 0x00020000);
+}
+// wave must be wave-uniform (scalar): it selects the LDS destination of each load
+__device__ inline void dt_load(dt_rsrc matrix, int tile_byte_offset, char* lds_tile, const uint32_t (&g)[4], int wave) {
 #pragma unroll
     for (int j = 0; j < 4; ++j)
-        __builtin_amdgcn_global_load_lds((global_char_t*)(gtile + g[j]),
-                                         (lds_char_t*)(lds_tile + (4 * wave + j) * 1024), 16, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(matrix, (lds_char_t*)(lds_tile + (4 * wave + j) * 1024), 16,
+                                                 (int)g[j], tile_byte_offset, 0, 0);
 }
 // A-operand row reads: address of row n (within a 32-row half tile), k-step ks, half h
 __device__ inline void dt_row_addrs(uint32_t (&a)[8], int n, int h) {
