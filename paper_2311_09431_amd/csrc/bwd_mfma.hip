@@ -48,7 +48,6 @@ __device__ inline bf16x8 pack8(const f32x16& x, int first) {
 // and then dQ^T += K(u)^T dS(u)^T (8 MFMA, K^T through the transposing LDS read).
 // Two barriers per 64-key tile: one makes the tile requested one iteration earlier
 // visible, one releases the tile just finished for the next request.
-constexpr int DQ_LDS_BYTES = 4 * DT_BYTES;       // K0, K1, V0, V1
 
 template <bool NEXT, bool MASK>
 __device__ inline void dq_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, f32x16& dp_next,
@@ -98,7 +97,12 @@ __device__ inline void dq_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, f3
 template <bool TRI>
 __global__ void __launch_bounds__(256, 2)
 bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
-    __shared__ __attribute__((aligned(1024))) char lds[DQ_LDS_BYTES];
+    // separate LDS objects per tile buffer: the compiler orders an LDS read after the direct
+    // loads in flight only when both touch the same object
+    __shared__ __attribute__((aligned(1024))) char k_lds0[DT_BYTES];
+    __shared__ __attribute__((aligned(1024))) char k_lds1[DT_BYTES];
+    __shared__ __attribute__((aligned(1024))) char v_lds0[DT_BYTES];
+    __shared__ __attribute__((aligned(1024))) char v_lds1[DT_BYTES];
 
     const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, h = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform, kept scalar
@@ -124,12 +128,10 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
     dt_row_addrs(arow, n, h);
     dt_tr_addrs(tr0, tr1, lane);
     dt_load_offsets(gl, lane, wave);
-    char* const kbuf = lds;
-    char* const vbuf = lds + 2 * DT_BYTES;
-    dt_load(Kr, 0, kbuf, gl, wave);
-    dt_load(Vr, 0, vbuf, gl, wave);
-    dt_load(Kr, DT_BYTES, kbuf + DT_BYTES, gl, wave);       // n_kt >= 2 always
-    dt_load(Vr, DT_BYTES, vbuf + DT_BYTES, gl, wave);
+    dt_load(Kr, 0, k_lds0, gl, wave);
+    dt_load(Vr, 0, v_lds0, gl, wave);
+    dt_load(Kr, DT_BYTES, k_lds1, gl, wave);       // n_kt >= 2 always
+    dt_load(Vr, DT_BYTES, v_lds1, gl, wave);
 
     bf16x8 qf[8], gf[8];
     load_b_frags(qf, Q + (int64_t)a * D, h);
@@ -152,8 +154,8 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
         for (int r = 0; r < 16; ++r) s_a[r] = dp_a[r] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
-            s_a = mfma(dt_read_row(kbuf, arow[ks]), qf[ks], s_a);
-            dp_a = mfma(dt_read_row(vbuf, arow[ks]), gf[ks], dp_a);
+            s_a = mfma(dt_read_row(k_lds0, arow[ks]), qf[ks], s_a);
+            dp_a = mfma(dt_read_row(v_lds0, arow[ks]), gf[ks], dp_a);
         }
     }
 
@@ -162,10 +164,10 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
     auto trip = [&](auto last_c, auto mask_c, auto par_c, int t) {
         constexpr bool LAST = decltype(last_c)::value, MASK = decltype(mask_c)::value;
         constexpr int PAR = decltype(par_c)::value;
-        const char* k_cur = kbuf + PAR * DT_BYTES;
-        const char* v_cur = vbuf + PAR * DT_BYTES;
-        const char* k_nxt = kbuf + (PAR ^ 1) * DT_BYTES;
-        const char* v_nxt = vbuf + (PAR ^ 1) * DT_BYTES;
+        char* const k_cur = PAR ? k_lds1 : k_lds0;
+        char* const v_cur = PAR ? v_lds1 : v_lds0;
+        char* const k_nxt = PAR ? k_lds0 : k_lds1;
+        char* const v_nxt = PAR ? v_lds0 : v_lds1;
         dq_step<true, MASK>(s_a, dp_a, s_b, dp_b, acc, qf, gf, kappa, lse2, delta, arow, tr0, tr1,
                             k_cur + DT_BYTES / 2, v_cur + DT_BYTES / 2, k_cur, mask_base - 64 * t);
         if (!LAST) {
@@ -177,8 +179,8 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
         if (!LAST) {
             __syncthreads();                    // every wavefront is done with tile t
             if (t + 2 < n_kt) {
-                dt_load(Kr, (t + 2) * DT_BYTES, kbuf + PAR * DT_BYTES, gl, wave);
-                dt_load(Vr, (t + 2) * DT_BYTES, vbuf + PAR * DT_BYTES, gl, wave);
+                dt_load(Kr, (t + 2) * DT_BYTES, k_cur, gl, wave);
+                dt_load(Vr, (t + 2) * DT_BYTES, v_cur, gl, wave);
             }
         }
     };
@@ -243,7 +245,6 @@ __device__ inline void mfma_vgpr_acc(f32x16& acc, bf16x8 a, bf16x8 b) {
 //     P(u) = exp2(S(u) kappa - LSE), dS(u) = P (dP(u) - delta)   (VALU)
 // and then dV^T += dO(u)^T P(u), dK^T += Q(u)^T dS(u) (16 MFMA, the transposed
 // operands through the transposing LDS read).
-constexpr int KV_TILES_BYTES = 4 * DT_BYTES;                 // Q0, Q1, dO0, dO1
 constexpr int KV_STAT_FLOATS = 2 * 2 * DT_ROWS;              // [buffer][lse2 | delta][64]
 
 template <bool NEXT, bool MASK>
@@ -315,7 +316,11 @@ __device__ inline void dkdv_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, 
 template <bool TRI>
 __global__ void __launch_bounds__(256, 1)
 bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
-    __shared__ __attribute__((aligned(1024))) char lds[KV_TILES_BYTES];
+    // separate LDS objects per tile buffer (see the dQ kernel)
+    __shared__ __attribute__((aligned(1024))) char q_lds0[DT_BYTES];
+    __shared__ __attribute__((aligned(1024))) char q_lds1[DT_BYTES];
+    __shared__ __attribute__((aligned(1024))) char g_lds0[DT_BYTES];
+    __shared__ __attribute__((aligned(1024))) char g_lds1[DT_BYTES];
     __shared__ __attribute__((aligned(16))) float stat[KV_STAT_FLOATS];
 
     const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, h = lane >> 5;
@@ -347,26 +352,27 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
     dt_row_addrs(arow, n, h);
     dt_tr_addrs(tr0, tr1, lane);
     dt_load_offsets(gl, lane, wave);
-    char* const qbuf = lds;
-    char* const gbuf = lds + 2 * DT_BYTES;
-    const bool two = t_first + 1 < n_qt;
-    dt_load(Qr, t_first * DT_BYTES, qbuf + (t_first & 1) * DT_BYTES, gl, wave);
-    dt_load(Gr, t_first * DT_BYTES, gbuf + (t_first & 1) * DT_BYTES, gl, wave);
-    if (two) {
-        dt_load(Qr, (t_first + 1) * DT_BYTES, qbuf + ((t_first + 1) & 1) * DT_BYTES, gl, wave);
-        dt_load(Gr, (t_first + 1) * DT_BYTES, gbuf + ((t_first + 1) & 1) * DT_BYTES, gl, wave);
-    }
-    // statistics of query tile t -> stat[(t & 1)][0 | 1][64]: threads 0..63 LSE * log2(e), 64..127 delta
-    auto stat_fetch = [&](int t) -> float {
-        if (tid < DT_ROWS) return LSE[t * DT_ROWS + tid] * LOG2E;
-        if (tid < 2 * DT_ROWS) return DEL[t * DT_ROWS + tid - DT_ROWS];
-        return 0.f;
+    // t_first and n_qt are even (k0 and c are multiples of 128): tile t_first goes to buffer 0
+    // and there are always at least two tiles
+    dt_load(Qr, t_first * DT_BYTES, q_lds0, gl, wave);
+    dt_load(Gr, t_first * DT_BYTES, g_lds0, gl, wave);
+    dt_load(Qr, (t_first + 1) * DT_BYTES, q_lds1, gl, wave);
+    dt_load(Gr, (t_first + 1) * DT_BYTES, g_lds1, gl, wave);
+    // statistics of query tile t -> stat[(t & 1)][0 | 1][64]: threads 0..63 LSE * log2(e), 64..127
+    // delta.  The fetch is branch-free (wavefronts 2 and 3 re-read what 0 and 1 read and drop
+    // it), so nothing waits for it before the store one trip later.
+    const float* stat_src = ((tid & DT_ROWS) ? DEL : LSE) + (tid & (DT_ROWS - 1)) + t_first * DT_ROWS;
+    const float stat_mul = (tid & DT_ROWS) ? 1.f : LOG2E;
+    auto stat_fetch = [&]() -> float {          // tiles in order: the pointer walks with them
+        const float x = *stat_src;
+        stat_src += DT_ROWS;
+        return x;
     };
     auto stat_store = [&](int t, float x) {
-        if (tid < 2 * DT_ROWS) stat[(t & 1) * 2 * DT_ROWS + tid] = x;
+        if (tid < 2 * DT_ROWS) stat[(t & 1) * 2 * DT_ROWS + tid] = x * stat_mul;
     };
-    stat_store(t_first, stat_fetch(t_first));
-    if (two) stat_store(t_first + 1, stat_fetch(t_first + 1));
+    stat_store(t_first, stat_fetch());
+    stat_store(t_first + 1, stat_fetch());
 
     bf16x8 kf[8], vf[8];
     load_b_frags(kf, K + (int64_t)key * D, h);
@@ -383,8 +389,8 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
 
     f32x16 s_a, s_b, dp_a, dp_b;
     {   // prologue: S, dP of the first sub-tile
-        const char* q0p = qbuf + (t_first & 1) * DT_BYTES;
-        const char* g0p = gbuf + (t_first & 1) * DT_BYTES;
+        const char* q0p = q_lds0;
+        const char* g0p = g_lds0;
         mfma_vgpr_first(s_a, dt_read_row(q0p, arow[0]), kf[0]);
         mfma_vgpr_first(dp_a, dt_read_row(g0p, arow[0]), vf[0]);
 #pragma unroll
@@ -397,14 +403,15 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
 
     float rstat = 0.f;          // statistics of the tile after next, in flight
     // Trip t = iterations 2t (scores in *_a) and 2t+1 (scores in *_b) on query tile t.
-    auto trip = [&](auto mask_c, auto par_c, int t) {
-        constexpr bool MASK = decltype(mask_c)::value;
+    // LAST is a compile-time flag: a trip that may or may not wait would leave the compiler
+    // unsure, at the top of the loop, whether the direct loads of the previous trip landed.
+    auto trip = [&](auto mask_c, auto par_c, auto last_c, int t) {
+        constexpr bool MASK = decltype(mask_c)::value, last = decltype(last_c)::value;
         constexpr int PAR = decltype(par_c)::value;
-        const bool last = t + 1 == n_qt;
-        const char* q_cur = qbuf + PAR * DT_BYTES;
-        const char* g_cur = gbuf + PAR * DT_BYTES;
-        const char* q_nxt = qbuf + (PAR ^ 1) * DT_BYTES;
-        const char* g_nxt = gbuf + (PAR ^ 1) * DT_BYTES;
+        char* const q_cur = PAR ? q_lds1 : q_lds0;
+        char* const g_cur = PAR ? g_lds1 : g_lds0;
+        char* const q_nxt = PAR ? q_lds0 : q_lds1;
+        char* const g_nxt = PAR ? g_lds0 : g_lds1;
         const float* st = stat + PAR * 2 * DT_ROWS;
         dkdv_step<true, MASK>(s_a, dp_a, s_b, dp_b, acck, accv, kf, vf, kappa, arow, tr0, tr1,
                               q_cur + DT_BYTES / 2, g_cur + DT_BYTES / 2, q_cur, g_cur, st, h,
@@ -418,11 +425,14 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
                                   mask_base - 64 * t - 32);
             __syncthreads();                     // every wavefront is done with tile t
             if (t + 2 < n_qt) {
-                dt_load(Qr, (t + 2) * DT_BYTES, qbuf + PAR * DT_BYTES, gl, wave);
-                dt_load(Gr, (t + 2) * DT_BYTES, gbuf + PAR * DT_BYTES, gl, wave);
-                rstat = stat_fetch(t + 2);
+                dt_load(Qr, (t + 2) * DT_BYTES, q_cur, gl, wave);
+                dt_load(Gr, (t + 2) * DT_BYTES, g_cur, gl, wave);
+                rstat = stat_fetch();
             }
         } else {
+            // nothing is in flight here; saying so keeps the loop above free of waits for
+            // loads that the (impossible) path last trip -> loop would leave pending
+            __builtin_amdgcn_s_waitcnt(0x0f70);          // vmcnt(0) only
             dkdv_step<false, MASK>(s_b, dp_b, s_a, dp_a, acck, accv, kf, vf, kappa, arow, tr0, tr1, q_nxt,
                                    g_nxt, q_cur + DT_BYTES / 2, g_cur + DT_BYTES / 2, st + 32, h,
                                    mask_base - 64 * t - 32);
@@ -432,17 +442,28 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
     using F = std::false_type;
     using P0 = std::integral_constant<int, 0>;
     using P1 = std::integral_constant<int, 1>;
-    int t = t_first;                             // even for triangular steps (k0 is a multiple of 128)
+    // t_first and n_qt are even (c and k0 are multiples of 128): trips come in pairs and the
+    // last one has odd parity
+    int t = t_first;
     if (TRI) {                                   // the first two trips carry the element mask
-        trip(T{}, P0{}, t);
-        if (t + 1 < n_qt) trip(T{}, P1{}, t + 1);
+        trip(T{}, P0{}, F{}, t);
+        if (t + 2 < n_qt) trip(T{}, P1{}, F{}, t + 1);
+        else trip(T{}, P1{}, T{}, t + 1);
         t += 2;
+        // The compiler lays the two alternatives above out one after the other and sees a
+        // path that takes neither, on which the loads of the first masked trip would still be
+        // in flight at the loop below; one wait here (once per workgroup) rules that out and
+        // keeps the loop itself free of waits right after its own loads.
+        __builtin_amdgcn_s_waitcnt(0x0f70);              // vmcnt(0) only
     }
-    for (; t + 1 < n_qt; t += 2) {
-        trip(F{}, P0{}, t);
-        trip(F{}, P1{}, t + 1);
+    for (; t + 2 < n_qt; t += 2) {
+        trip(F{}, P0{}, F{}, t);
+        trip(F{}, P1{}, F{}, t + 1);
     }
-    if (t < n_qt) trip(F{}, P0{}, t);
+    if (t < n_qt) {
+        trip(F{}, P0{}, F{}, t);
+        trip(F{}, P1{}, T{}, t + 1);
+    }
 
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb)

@@ -58,9 +58,6 @@ constexpr int BM = 32 * NW;             // query rows per workgroup
 constexpr int D = TD;                   // head dimension
 constexpr int TILE_ROWS = 64;           // key rows per LDS tile
 constexpr int TILE_BYTES = TILE_ROWS * D * 2;   // 16 KiB
-constexpr int K_BUF0 = 0;               // two K tiles, then two V tiles
-constexpr int V_BUF0 = 2 * TILE_BYTES;
-constexpr int LDS_BYTES = 4 * TILE_BYTES;
 constexpr float RESCALE_LOG2 = 8.f;
 
 typedef __attribute__((address_space(3))) char lds_char;
@@ -165,7 +162,13 @@ __device__ inline void step(f32x16& s_cur, f32x16& s_next, bf16x8 (&p_cur)[2], b
 template <bool TRI>
 __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1)
 fwd_mfma_kernel(StepArgs p, int n_qtiles) {
-    __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
+    // four separate LDS objects, not one array: the compiler orders an LDS read after the
+    // direct loads in flight only when both touch the same object, so reads of one tile do
+    // not wait for the loads of another
+    __shared__ __attribute__((aligned(1024))) char k_lds0[TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char k_lds1[TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char v_lds0[TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char v_lds1[TILE_BYTES];
 
     const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, h = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform, kept scalar
@@ -213,9 +216,9 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     }
 
     // first tiles on their way while the running state is loaded
-    load_tile_direct(K, 0, lds + K_BUF0, kg, wave);
-    load_tile_direct(V, 0, lds + V_BUF0, vg, wave);
-    load_tile_direct(K, TILE_BYTES, lds + K_BUF0 + TILE_BYTES, kg, wave);     // n_kt >= 2 always
+    load_tile_direct(K, 0, k_lds0, kg, wave);
+    load_tile_direct(V, 0, v_lds0, vg, wave);
+    load_tile_direct(K, TILE_BYTES, k_lds1, kg, wave);     // n_kt >= 2 always
 
     bf16x8 qf[8];
     load_b_frags(qf, Q + (int64_t)a * D, h);
@@ -246,7 +249,7 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) s_a[r] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) s_a = mfma(lds_read_b128(lds + K_BUF0, kaddr[ks]), qf[ks], s_a);
+        for (int ks = 0; ks < 8; ++ks) s_a = mfma(lds_read_b128(k_lds0, kaddr[ks]), qf[ks], s_a);
     }
 
     // Trip t = iterations u = 2t and 2t+1 with barrier t between them.  Iteration u does
@@ -260,16 +263,16 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
         constexpr bool FIRST = decltype(first_c)::value, LAST = decltype(last_c)::value;
         constexpr bool MASK = decltype(mask_c)::value;
         constexpr int PAR = decltype(par_c)::value;
-        const char* k_cur = lds + K_BUF0 + PAR * TILE_BYTES;
-        const char* k_nxt = lds + K_BUF0 + (PAR ^ 1) * TILE_BYTES;
-        const char* v_cur = lds + V_BUF0 + PAR * TILE_BYTES;
-        const char* v_prv = lds + V_BUF0 + (PAR ^ 1) * TILE_BYTES;
+        char* const k_cur = PAR ? k_lds1 : k_lds0;
+        char* const k_nxt = PAR ? k_lds0 : k_lds1;
+        char* const v_cur = PAR ? v_lds1 : v_lds0;
+        char* const v_prv = PAR ? v_lds0 : v_lds1;
         step<true, true, !FIRST, MASK>(s_a, s_b, p_a, p_b, oacc, qf, m, l, kappa, kaddr, vaddr,
                                        k_cur + TILE_BYTES / 2, v_prv + TILE_BYTES / 2, mask_base - 64 * t);
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-        if (t + 2 < n_kt) load_tile_direct(K, (t + 2) * TILE_BYTES, lds + K_BUF0 + PAR * TILE_BYTES, kg, wave);
-        if (t + 1 < n_kt) load_tile_direct(V, (t + 1) * TILE_BYTES, lds + V_BUF0 + (PAR ^ 1) * TILE_BYTES, vg, wave);
+        if (t + 2 < n_kt) load_tile_direct(K, (t + 2) * TILE_BYTES, k_cur, kg, wave);
+        if (t + 1 < n_kt) load_tile_direct(V, (t + 1) * TILE_BYTES, v_prv, vg, wave);
         step<!LAST, true, true, MASK>(s_b, s_a, p_b, p_a, oacc, qf, m, l, kappa, kaddr, vaddr, k_nxt, v_cur,
                                       mask_base - 64 * t - 32);
     };
@@ -307,7 +310,7 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     for (; t < n_kt; ++t) run(T{}, t);
     // final iteration u = 2 n_kt: PV(2 n_kt - 1): V tile n_kt - 1, second half; P in p_b
     {
-        const char* v_last = lds + V_BUF0 + ((n_kt - 1) & 1) * TILE_BYTES + TILE_BYTES / 2;
+        const char* v_last = (((n_kt - 1) & 1) ? v_lds1 : v_lds0) + TILE_BYTES / 2;
         step<false, false, true, false>(s_a, s_b, p_a, p_b, oacc, qf, m, l, kappa, kaddr, vaddr, v_last, v_last, 0);
     }
 
