@@ -97,8 +97,7 @@ __device__ inline void dq_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, f3
 template <bool TRI>
 __global__ void __launch_bounds__(256, 2)
 bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
-    // separate LDS objects per tile buffer: the compiler orders an LDS read after the direct
-    // loads in flight only when both touch the same object
+    // one LDS object per tile buffer
     __shared__ __attribute__((aligned(1024))) char k_lds0[DT_BYTES];
     __shared__ __attribute__((aligned(1024))) char k_lds1[DT_BYTES];
     __shared__ __attribute__((aligned(1024))) char v_lds0[DT_BYTES];
@@ -137,14 +136,17 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
     load_b_frags(qf, Q + (int64_t)a * D, h);
     load_b_frags(gf, G + (int64_t)a * D, h);
     const float kappa = p.scale * LOG2E;
-    const float lse2 = p.lse[sbase + a] * LOG2E;
-    const float delta = p.delta[sbase + a];
+    float lse2 = p.lse[sbase + a] * LOG2E;
+    float delta = p.delta[sbase + a];
     f32x16 acc[4];
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[mb][r] = 0.f;
 
+    // the statistics are complete here: a load left pending into the loop would be waited
+    // for there, together with the tile loads just issued
+    asm volatile("" : "+v"(lse2), "+v"(delta));
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
@@ -316,7 +318,7 @@ __device__ inline void dkdv_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, 
 template <bool TRI>
 __global__ void __launch_bounds__(256, 1)
 bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
-    // separate LDS objects per tile buffer (see the dQ kernel)
+    // one LDS object per tile buffer
     __shared__ __attribute__((aligned(1024))) char q_lds0[DT_BYTES];
     __shared__ __attribute__((aligned(1024))) char q_lds1[DT_BYTES];
     __shared__ __attribute__((aligned(1024))) char g_lds0[DT_BYTES];
@@ -403,8 +405,6 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
 
     float rstat = 0.f;          // statistics of the tile after next, in flight
     // Trip t = iterations 2t (scores in *_a) and 2t+1 (scores in *_b) on query tile t.
-    // LAST is a compile-time flag: a trip that may or may not wait would leave the compiler
-    // unsure, at the top of the loop, whether the direct loads of the previous trip landed.
     auto trip = [&](auto mask_c, auto par_c, auto last_c, int t) {
         constexpr bool MASK = decltype(mask_c)::value, last = decltype(last_c)::value;
         constexpr int PAR = decltype(par_c)::value;
@@ -430,9 +430,6 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
                 rstat = stat_fetch();
             }
         } else {
-            // nothing is in flight here; saying so keeps the loop above free of waits for
-            // loads that the (impossible) path last trip -> loop would leave pending
-            __builtin_amdgcn_s_waitcnt(0x0f70);          // vmcnt(0) only
             dkdv_step<false, MASK>(s_b, dp_b, s_a, dp_a, acck, accv, kf, vf, kappa, arow, tr0, tr1, q_nxt,
                                    g_nxt, q_cur + DT_BYTES / 2, g_cur + DT_BYTES / 2, st + 32, h,
                                    mask_base - 64 * t - 32);
@@ -450,11 +447,6 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
         if (t + 2 < n_qt) trip(T{}, P1{}, F{}, t + 1);
         else trip(T{}, P1{}, T{}, t + 1);
         t += 2;
-        // The compiler lays the two alternatives above out one after the other and sees a
-        // path that takes neither, on which the loads of the first masked trip would still be
-        // in flight at the loop below; one wait here (once per workgroup) rules that out and
-        // keeps the loop itself free of waits right after its own loads.
-        __builtin_amdgcn_s_waitcnt(0x0f70);              // vmcnt(0) only
     }
     for (; t + 2 < n_qt; t += 2) {
         trip(F{}, P0{}, F{}, t);

@@ -5,7 +5,7 @@
 //
 // Work decomposition.  A workgroup of 4 wavefronts owns 128 query rows; each
 // wavefront owns 32 of them for the whole kernel.  Key/value tiles of 64 rows
-// stream from global memory straight into LDS (global_load_lds, no register
+// stream from global memory straight into LDS (buffer_load ... lds, no register
 // staging), two buffers each for K and V, one barrier per tile.
 //
 // The scores are computed TRANSPOSED, S^T = K Q^T (A = key rows from LDS, B = the
@@ -70,9 +70,7 @@ constexpr int LPW = 16 / NW;             // direct loads per wavefront and tile
 __device__ inline void load_tile_direct(dt_rsrc matrix, int tile_byte_offset, char* lds_tile, const uint32_t (&g)[4],
                                         int wave) {
 #pragma unroll
-    for (int j = 0; j < LPW; ++j)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(matrix, (lds_char*)(lds_tile + (LPW * wave + j) * 1024), 16,
-                                                 (int)g[j], tile_byte_offset, 0, 0);
+    for (int j = 0; j < LPW; ++j) dt_load_piece(matrix, tile_byte_offset, g[j], lds_tile + (LPW * wave + j) * 1024);
 }
 
 __device__ inline bf16x8 lds_read_b128(const char* lds, uint32_t addr) {
@@ -162,9 +160,7 @@ __device__ inline void step(f32x16& s_cur, f32x16& s_next, bf16x8 (&p_cur)[2], b
 template <bool TRI>
 __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1)
 fwd_mfma_kernel(StepArgs p, int n_qtiles) {
-    // four separate LDS objects, not one array: the compiler orders an LDS read after the
-    // direct loads in flight only when both touch the same object, so reads of one tile do
-    // not wait for the loads of another
+    // one LDS object per tile buffer
     __shared__ __attribute__((aligned(1024))) char k_lds0[TILE_BYTES];
     __shared__ __attribute__((aligned(1024))) char k_lds1[TILE_BYTES];
     __shared__ __attribute__((aligned(1024))) char v_lds0[TILE_BYTES];

@@ -83,7 +83,7 @@ __device__ inline bf16x8 read_a_trn(const __bf16* lds_tile, int col, int g, int 
 // ---------------------------------------------------------------------------
 // Swizzled tiles filled by direct global -> LDS loads.
 //
-// A tile is 64 rows x 256 bytes (128 bf16) with NO padding: global_load_lds
+// A tile is 64 rows x 256 bytes (128 bf16) with NO padding: a direct load
 // writes the 64 lanes' 16-byte pieces contiguously (1 KiB per wavefront
 // instruction, 4 rows), so a 16 KiB tile takes 16 instructions, 4 per
 // wavefront.  Bank conflicts are avoided by storing the 16-byte chunk c of row
@@ -123,17 +123,43 @@ __device__ inline void dt_load_offsets(uint32_t (&g)[4], int lane, int wave) {
 // The loads go through a buffer descriptor held in scalar registers: the tile's byte
 // offset within the (batch, head) matrix is a scalar operand and the lane offset a 32-bit
 // vector operand, so a load costs no address arithmetic at all.  The descriptor's range is
-// the c rows of the matrix.
-typedef __amdgpu_buffer_rsrc_t dt_rsrc;
+// the c rows of the matrix (stride 0, raw 32-bit data format).
+//
+// The instruction is issued from inline assembly on purpose.  The compiler orders LDS reads
+// after a direct load it knows about with a conservative model of what the load writes, and
+// puts a wait for ALL loads in flight in front of reads of a different buffer, i.e. right
+// after the loads were issued.  Issued this way the loads are invisible to that model; the
+// kernels order them by hand: s_waitcnt vmcnt(0) followed by a workgroup barrier before a
+// buffer is read, a barrier after its last read before it is requested again.  The
+// "memory" clobber keeps the compiler from moving LDS accesses across the request.
+typedef int dt_rsrc __attribute__((ext_vector_type(4)));
 __device__ inline dt_rsrc dt_make_rsrc(const void* matrix, int rows) {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(matrix), 0, rows * (TD * 2), 0x00020000);
+    const uint64_t a = reinterpret_cast<uint64_t>(matrix);
+    dt_rsrc r;
+    r[0] = (int)(uint32_t)a;
+    r[1] = (int)((uint32_t)(a >> 32) & 0xffffu);
+    r[2] = rows * (TD * 2);
+    r[3] = 0x00020000;
+    return r;
 }
+// one 1 KiB piece: 64 lanes x 16 bytes from matrix + tile_byte_offset + lane_offset to
+// lds_dst + 16 * lane (lds_dst wave-uniform)
+// (m0 is named as clobbered although the compiler calls it reserved: nothing else in these
+// kernels uses it, and the note it prints about that is switched off for this function)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ inline void dt_load_piece(dt_rsrc matrix, int tile_byte_offset, uint32_t lane_offset, const char* lds_dst) {
+    const uint32_t dst = (uint32_t)reinterpret_cast<uintptr_t>((const lds_char_t*)lds_dst);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(dst), "v"(lane_offset), "s"(matrix), "s"(tile_byte_offset)
+                 : "memory", "m0");
+}
+#pragma clang diagnostic pop
 // wave must be wave-uniform (scalar): it selects the LDS destination of each load
 __device__ inline void dt_load(dt_rsrc matrix, int tile_byte_offset, char* lds_tile, const uint32_t (&g)[4], int wave) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(matrix, (lds_char_t*)(lds_tile + (4 * wave + j) * 1024), 16,
-                                                 (int)g[j], tile_byte_offset, 0, 0);
+    for (int j = 0; j < 4; ++j) dt_load_piece(matrix, tile_byte_offset, g[j], lds_tile + (4 * wave + j) * 1024);
 }
 // A-operand row reads: address of row n (within a 32-row half tile), k-step ks, half h
 __device__ inline void dt_row_addrs(uint32_t (&a)[8], int n, int h) {
