@@ -30,9 +30,17 @@ from paper_2311_09431_amd import inputs           # noqa: E402
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
-# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this workload
-# (see profiles/); None until measured for a kernel
-TRAFFIC = {}
+# HBM bytes per launch (one triangular step of the cfg3 workload) measured with rocprofv3 --pmc
+# FETCH_SIZE (x2, calibrated on the copy kernel) and WRITE_SIZE, see
+# profiles/ring_step_kernels_cfg3.txt; only valid for that workload
+TRAFFIC = {
+    "cfg3": {
+        "fwd ring step (fwd_mfma_kernel)":
+            {"read_GB": 5.07, "written_GB": 1.17, "algorithmic_GB": 1.89},
+        "bwd ring step (bwd_dq_mfma_kernel + bwd_dkdv_mfma_kernel)":
+            {"read_GB": 8.06, "written_GB": 1.61, "algorithmic_GB": 5.37},
+    },
+}
 
 # one device's share: the worst-loaded query device of both layouts is N-1
 WORKLOADS = {
@@ -142,6 +150,14 @@ def cpu_baseline(seconds_budget=20.0):
                        (S, flops / 1e9))
 
 
+def traffic_fields(workload, name):
+    t = TRAFFIC.get(workload, {}).get(name)
+    if t is None:
+        return dict(traffic=None)
+    # bytes per launch (read + written), with the split and the algorithmic figure beside it
+    return dict(traffic=int(round((t["read_GB"] + t["written_GB"]) * 1e9)), traffic_detail=t)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -202,7 +218,7 @@ def main():
         tot_ms = sum(r["ms"] for r in live)
         ach = sum(r["tflops"] * r["ms"] for r in live) / max(1e-9, tot_ms)
         return dict(bound="mfma", kernel=name, achieved=round(ach, 1), peak=PEAK_BF16_TFLOPS,
-                    unit="TFLOP/s", frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=TRAFFIC.get(name),
+                    unit="TFLOP/s", frac=round(ach / PEAK_BF16_TFLOPS, 4), **traffic_fields(args.workload, name),
                     avg_launch_ms=round(tot_ms / max(1, len(live)), 4), total_ms=round(tot_ms, 3))
     roofs = {"fwd": roof(striped_rows, "fwd ring step (fwd_mfma_kernel)")}
     if args.bwd:

@@ -476,7 +476,9 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
 }  // namespace
 
 bool bwd_mfma_supported(const StepArgs& a, int dtype) {
-    return dtype == SA_BF16 && a.d == D && a.c % BM == 0;
+    // c <= 2^22 rows: a shard matrix (256 bytes per row) stays inside a buffer descriptor's
+    // 32-bit byte range with room to spare
+    return dtype == SA_BF16 && a.d == D && a.c % BM == 0 && a.c <= (1 << 22);
 }
 
 hipError_t launch_bwd_mfma(const StepArgs& a, hipStream_t st) {
