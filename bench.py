@@ -73,8 +73,8 @@ def useful_flops(w, layout, per_pair):
 
 
 class Runner:
-    def __init__(self, w, seed, bwd):
-        self.w, self.bwd = w, bwd
+    def __init__(self, w, seed, bwd, skip=(0, 0)):
+        self.w, self.bwd, self.skip = w, bwd, skip
         B, H, S, d, N = w["B"], w["H"], w["S"], w["d"], w["N"]
         dev = "cuda"
         n_in = 4 if bwd else 3
@@ -99,15 +99,17 @@ class Runner:
             ins = self.perm
         else:
             ins = self.orig
-        t_f = sa.sa_ring_fwd(ins[0], ins[1], ins[2], self.O, self.LSE, w["N"], layout, self.shape,
-                             w["q_dev"], timed)
+        bq, bk = self.skip      # (0, 0): the kernels' own skipping granularity
+        t_f = sa.sa_ring_fwd_tiled(ins[0], ins[1], ins[2], self.O, self.LSE, w["N"], layout, self.shape,
+                                   bq, bk, w["q_dev"], timed)
         devs = range(w["N"]) if w["q_dev"] < 0 else [w["q_dev"]]
         for j in devs:
             sa.sa_finalize(self.O[:, :, j * c:], self.out[:, :, j * c:], self.shape)
         t_b = None
         if self.bwd:
-            t_b = sa.sa_ring_bwd(ins[0], ins[1], ins[2], ins[3], self.O, self.LSE, self.delta, self.dQ,
-                                 self.dK, self.dV, w["N"], layout, self.shape, w["q_dev"], timed)
+            t_b = sa.sa_ring_bwd_tiled(ins[0], ins[1], ins[2], ins[3], self.O, self.LSE, self.delta,
+                                       self.dQ, self.dK, self.dV, w["N"], layout, self.shape, bq, bk,
+                                       w["q_dev"], timed)
         return t_f, t_b
 
 
@@ -167,7 +169,13 @@ def main():
     ap.add_argument("--bwd", type=int, default=1, help="0: forward ring only (default: forward + backward)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=3)
+    ap.add_argument("--skip-granularity", default="", metavar="BQxBK",
+                    help="emulate tile skipping per BQ x BK tile (Sec. 3.1 of the paper), e.g. 2048x4096; "
+                         "default: the kernels' own 32 x 32")
     args = ap.parse_args()
+    skip = tuple(int(x) for x in args.skip_granularity.lower().split("x")) if args.skip_granularity else (0, 0)
+    if len(skip) != 2:
+        ap.error("--skip-granularity takes BQxBK")
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (the ring's N devices are played in sequence on "
               "it); --gpus N > 1 is not supported", file=sys.stderr)
@@ -177,7 +185,7 @@ def main():
         sys.exit(1)
     sa.lib()
     w = WORKLOADS[args.workload]
-    run = Runner(w, args.seed, bool(args.bwd))
+    run = Runner(w, args.seed, bool(args.bwd), skip)
     torch.cuda.synchronize()
 
     for _ in range(args.warmup):
@@ -251,6 +259,22 @@ def main():
         result["striped"]["bwd_steps"], result["striped"]["bwd_worst_device_ms_per_round"] = rb, wb
         rb, wb = summarize_steps(w, sa.CONTIGUOUS, avg(ctab_b), 10)
         result["contiguous"]["bwd_steps"], result["contiguous"]["bwd_worst_device_ms_per_round"] = rb, wb
+    if skip != (0, 0):
+        from paper_2311_09431_amd import tms
+        c = w["S"] // N
+        if args.bwd:
+            tot = lambda r: sum(a + b for a, b in zip(r["worst_device_ms_per_round"],
+                                                      r["bwd_worst_device_ms_per_round"]))
+        else:
+            tot = lambda r: sum(r["worst_device_ms_per_round"])
+        result["skip_granularity"] = {
+            "tile_q": skip[0], "tile_k": skip[1],
+            "note": "useful TFLOP/s still count unmasked pairs only; masked parts of computed tiles are waste",
+            "worst_device_ratio_measured": round(tot(result["contiguous"]) / max(1e-9, tot(result["striped"])), 3),
+            "worst_device_ratio_computed_tiles": round(
+                tms.tiled_attention_limit(N, c, *skip, devices=None if w["q_dev"] < 0 else [w["q_dev"]]), 3),
+            "worst_device_ratio_element_granularity": round(tms.attention_only_limit(N, c), 3),
+        }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline()
     print(json.dumps(result))

@@ -153,6 +153,34 @@ int sa_ring_bwd(const void* Q, const void* K, const void* V, const void* dO, con
                 void* stream);
 
 /*
+ * Emulated tile-skipping granularity (Sec. 3.1, 3.2: the paper's implementation skips work
+ * per 2048 x 4096 or 2048 x 2048 tile of a block).  The *_tiled variants compute the SAME
+ * result as sa_attn_step_fwd / sa_attn_step_bwd / sa_ring_fwd / sa_ring_bwd, bit for bit,
+ * but do the work of a skip_bq (queries) x skip_bk (keys) tile in full as soon as the tile
+ * holds one allowed pair (masked elements inside contribute exact zeros), and skip it only
+ * if it holds none.  They exist to measure what striping gains at a given granularity, to
+ * set beside the paper's tables; skip_bq = skip_bk = 0 selects the kernels' own granularity
+ * (32 x 32) and is what the plain entry points do.  Otherwise both must be multiples of 128
+ * that divide c, and the shape must be one the MFMA kernels take (bf16, d = 128,
+ * c % 128 == 0); anything else returns SA_ERR_SHAPE.  All other arguments as in the plain
+ * entry points.
+ */
+int sa_attn_step_fwd_tiled(const void* q, const void* k, const void* v, float* o, float* lse,
+                           int32_t q_dev, int32_t kv_dev, int32_t N, int32_t layout,
+                           const sa_shape* shape, int32_t skip_bq, int32_t skip_bk, void* stream);
+int sa_attn_step_bwd_tiled(const void* q, const void* k, const void* v, const void* dout,
+                           const float* lse, const float* delta, float* dq, float* dk, float* dv,
+                           int32_t q_dev, int32_t kv_dev, int32_t N, int32_t layout,
+                           const sa_shape* shape, int32_t skip_bq, int32_t skip_bk, void* stream);
+int sa_ring_fwd_tiled(const void* Q, const void* K, const void* V, float* O, float* LSE, int32_t N,
+                      int32_t layout, const sa_shape* shape, int32_t skip_bq, int32_t skip_bk,
+                      int32_t q_dev_only, float* step_ms, void* stream);
+int sa_ring_bwd_tiled(const void* Q, const void* K, const void* V, const void* dO, const float* O,
+                      const float* LSE, float* delta, float* dQ, float* dK, float* dV, int32_t N,
+                      int32_t layout, const sa_shape* shape, int32_t skip_bq, int32_t skip_bk,
+                      int32_t q_dev_only, float* step_ms, void* stream);
+
+/*
  * Host-only helpers (no GPU work).
  * sa_mask_offset: the step's mask as "allowed iff b <= a - off": returns 0 and
  * writes *off (0 or 1), or writes *kind = 0 empty / 1 triangular / 2 full.
@@ -162,6 +190,13 @@ int sa_ring_bwd(const void* Q, const void* K, const void* V, const void* dO, con
 int sa_step_mask(int32_t q_dev, int32_t kv_dev, int32_t N, int32_t layout, int32_t* kind,
                  int32_t* off);
 int64_t sa_step_pairs(int32_t q_dev, int32_t kv_dev, int32_t N, int32_t layout, int64_t c);
+/*
+ * sa_step_tiles: the step's c x c block cut into skip_bq x skip_bk tiles (Sec. 2.2.1): *total =
+ * number of tiles, *computed = those with at least one allowed pair (the rest are skipped,
+ * Sec. 3.1).  Any positive sizes dividing c.  Errors: NULL, DEV, LAYOUT, SHAPE.
+ */
+int sa_step_tiles(int32_t q_dev, int32_t kv_dev, int32_t N, int32_t layout, int64_t c,
+                  int64_t skip_bq, int64_t skip_bk, int64_t* computed, int64_t* total);
 
 /* Human-readable name of a status code; never NULL. */
 const char* sa_status_str(int status);

@@ -52,6 +52,12 @@ def lib():
             "sa_attn_step_bwd": (i32, [vp] * 9 + [i32, i32, i32, i32, shp, vp]),
             "sa_ring_fwd": (i32, [vp] * 5 + [i32, i32, shp, i32, vp, vp]),
             "sa_ring_bwd": (i32, [vp] * 10 + [i32, i32, shp, i32, vp, vp]),
+            "sa_attn_step_fwd_tiled": (i32, [vp, vp, vp, vp, vp, i32, i32, i32, i32, shp, i32, i32, vp]),
+            "sa_attn_step_bwd_tiled": (i32, [vp] * 9 + [i32, i32, i32, i32, shp, i32, i32, vp]),
+            "sa_ring_fwd_tiled": (i32, [vp] * 5 + [i32, i32, shp, i32, i32, i32, vp, vp]),
+            "sa_ring_bwd_tiled": (i32, [vp] * 10 + [i32, i32, shp, i32, i32, i32, vp, vp]),
+            "sa_step_tiles": (i32, [i32, i32, i32, i32, i64, i64, i64, ctypes.POINTER(i64),
+                                    ctypes.POINTER(i64)]),
             "sa_step_mask": (i32, [i32, i32, i32, i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]),
             "sa_step_pairs": (i64, [i32, i32, i32, i32, i64]),
             "sa_status_str": (ctypes.c_char_p, [i32]),
@@ -65,7 +71,8 @@ def lib():
 
 EXPORTS = ("sa_stripe_permute", "sa_unstripe_permute", "sa_state_init", "sa_attn_step_fwd",
            "sa_finalize", "sa_bwd_preprocess", "sa_attn_step_bwd", "sa_ring_fwd", "sa_ring_bwd",
-           "sa_step_mask", "sa_step_pairs", "sa_status_str")
+           "sa_attn_step_fwd_tiled", "sa_attn_step_bwd_tiled", "sa_ring_fwd_tiled", "sa_ring_bwd_tiled",
+           "sa_step_tiles", "sa_step_mask", "sa_step_pairs", "sa_status_str")
 
 
 def _ptr(t):
@@ -163,6 +170,45 @@ def sa_ring_bwd(Q, K, V, dO, O, LSE, delta, dQ, dK, dV, N, layout, shape, q_dev_
                              _ptr(dQ), _ptr(dK), _ptr(dV), N, layout, ctypes.byref(shape), q_dev_only,
                              buf, _stream()), "sa_ring_bwd")
     return [[buf[i * N + j] for j in range(N)] for i in range(N)] if timed else None
+
+
+def sa_attn_step_fwd_tiled(q, k, v, o, lse, q_dev, kv_dev, N, layout, shape, skip_bq, skip_bk):
+    _check(lib().sa_attn_step_fwd_tiled(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), q_dev, kv_dev, N,
+                                        layout, ctypes.byref(shape), skip_bq, skip_bk, _stream()),
+           "sa_attn_step_fwd_tiled")
+
+
+def sa_attn_step_bwd_tiled(q, k, v, dout, lse, delta, dq, dk, dv, q_dev, kv_dev, N, layout, shape,
+                           skip_bq, skip_bk):
+    _check(lib().sa_attn_step_bwd_tiled(_ptr(q), _ptr(k), _ptr(v), _ptr(dout), _ptr(lse), _ptr(delta),
+                                        _ptr(dq), _ptr(dk), _ptr(dv), q_dev, kv_dev, N, layout,
+                                        ctypes.byref(shape), skip_bq, skip_bk, _stream()),
+           "sa_attn_step_bwd_tiled")
+
+
+def sa_ring_fwd_tiled(Q, K, V, O, LSE, N, layout, shape, skip_bq, skip_bk, q_dev_only=-1, timed=False):
+    buf = (ctypes.c_float * (N * N))() if timed else None
+    _check(lib().sa_ring_fwd_tiled(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), N, layout,
+                                   ctypes.byref(shape), skip_bq, skip_bk, q_dev_only, buf, _stream()),
+           "sa_ring_fwd_tiled")
+    return [[buf[i * N + j] for j in range(N)] for i in range(N)] if timed else None
+
+
+def sa_ring_bwd_tiled(Q, K, V, dO, O, LSE, delta, dQ, dK, dV, N, layout, shape, skip_bq, skip_bk,
+                      q_dev_only=-1, timed=False):
+    buf = (ctypes.c_float * (N * N))() if timed else None
+    _check(lib().sa_ring_bwd_tiled(_ptr(Q), _ptr(K), _ptr(V), _ptr(dO), _ptr(O), _ptr(LSE), _ptr(delta),
+                                   _ptr(dQ), _ptr(dK), _ptr(dV), N, layout, ctypes.byref(shape), skip_bq,
+                                   skip_bk, q_dev_only, buf, _stream()), "sa_ring_bwd_tiled")
+    return [[buf[i * N + j] for j in range(N)] for i in range(N)] if timed else None
+
+
+def sa_step_tiles(q_dev, kv_dev, N, layout, c, skip_bq, skip_bk):
+    """(computed, total) tiles of the step's block at granularity skip_bq x skip_bk."""
+    computed, total = ctypes.c_int64(), ctypes.c_int64()
+    _check(lib().sa_step_tiles(q_dev, kv_dev, N, layout, c, skip_bq, skip_bk, ctypes.byref(computed),
+                               ctypes.byref(total)), "sa_step_tiles")
+    return computed.value, total.value
 
 
 def sa_step_mask(q_dev, kv_dev, N, layout):

@@ -69,12 +69,23 @@ int permute_common(const void* src, void* dst, int64_t outer, int64_t n_seq, int
                    hipSuccess ? SA_OK : SA_ERR_HIP;
 }
 
+// Emulated tile-skipping granularity (Sec. 3.1): both 0 (the kernels' own), or multiples of
+// 128 dividing c on a shape the MFMA kernels take.
+int check_skip(const sa_shape* s, int bq, int bk) {
+    if (bq == 0 && bk == 0) return SA_OK;
+    if (bq < 128 || bk < 128 || bq % 128 || bk % 128 || s->c % bq || s->c % bk) return SA_ERR_SHAPE;
+    StepArgs a = make_args(s);
+    return sa::fwd_mfma_supported(a, s->dtype) && sa::bwd_mfma_supported(a, s->dtype) ? SA_OK
+                                                                                      : SA_ERR_SHAPE;
+}
+
 int step_fwd(const void* q, const void* k, const void* v, float* o, float* lse, int q_dev, int kv_dev,
-             int layout, const sa_shape* s, hipStream_t st) {
+             int layout, const sa_shape* s, int bq, int bk, hipStream_t st) {
     StepArgs a = make_args(s);
     classify(q_dev, kv_dev, layout, &a.kind, &a.off);
     if (a.kind == sa::MASK_EMPTY) return SA_OK;   // entirely masked block: nothing to launch
     a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse;
+    a.skip_bq = bq; a.skip_bk = bk;
     hipError_t e = sa::fwd_mfma_supported(a, s->dtype) ? sa::launch_fwd_mfma(a, st)
                                                        : sa::launch_fwd_generic(a, s->dtype, st);
     return e == hipSuccess ? SA_OK : SA_ERR_HIP;
@@ -82,10 +93,11 @@ int step_fwd(const void* q, const void* k, const void* v, float* o, float* lse, 
 
 int step_bwd(const void* q, const void* k, const void* v, const void* dout, const float* lse,
              const float* delta, float* dq, float* dk, float* dv, int q_dev, int kv_dev, int layout,
-             const sa_shape* s, hipStream_t st) {
+             const sa_shape* s, int bq, int bk, hipStream_t st) {
     StepArgs a = make_args(s);
     classify(q_dev, kv_dev, layout, &a.kind, &a.off);
     if (a.kind == sa::MASK_EMPTY) return SA_OK;
+    a.skip_bq = bq; a.skip_bk = bk;
     a.q = q; a.k = k; a.v = v; a.dout = dout; a.lse = const_cast<float*>(lse); a.delta = delta;
     a.dq = dq; a.dk = dk; a.dv = dv;
     hipError_t e = sa::bwd_mfma_supported(a, s->dtype) ? sa::launch_bwd_mfma(a, st)
@@ -144,13 +156,20 @@ int sa_state_init(float* o, float* lse, const sa_shape* shape, void* stream) {
     return sa::launch_state_init(o, lse, *shape, (hipStream_t)stream) == hipSuccess ? SA_OK : SA_ERR_HIP;
 }
 
-int sa_attn_step_fwd(const void* q, const void* k, const void* v, float* o, float* lse, int32_t q_dev,
-                     int32_t kv_dev, int32_t N, int32_t layout, const sa_shape* shape, void* stream) {
+int sa_attn_step_fwd_tiled(const void* q, const void* k, const void* v, float* o, float* lse,
+                           int32_t q_dev, int32_t kv_dev, int32_t N, int32_t layout, const sa_shape* shape,
+                           int32_t skip_bq, int32_t skip_bk, void* stream) {
     if (!q || !k || !v || !o || !lse) return SA_ERR_NULL;
     if (int e = check_shape(shape)) return e;
     if (int e = check_step(q_dev, kv_dev, N, layout)) return e;
+    if (int e = check_skip(shape, skip_bq, skip_bk)) return e;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return SA_ERR_ALIGN;
-    return step_fwd(q, k, v, o, lse, q_dev, kv_dev, layout, shape, (hipStream_t)stream);
+    return step_fwd(q, k, v, o, lse, q_dev, kv_dev, layout, shape, skip_bq, skip_bk, (hipStream_t)stream);
+}
+
+int sa_attn_step_fwd(const void* q, const void* k, const void* v, float* o, float* lse, int32_t q_dev,
+                     int32_t kv_dev, int32_t N, int32_t layout, const sa_shape* shape, void* stream) {
+    return sa_attn_step_fwd_tiled(q, k, v, o, lse, q_dev, kv_dev, N, layout, shape, 0, 0, stream);
 }
 
 int sa_finalize(const float* o, void* out, const sa_shape* shape, void* stream) {
@@ -169,23 +188,34 @@ int sa_bwd_preprocess(const float* o, const void* dout, float* delta, const sa_s
                ? SA_OK : SA_ERR_HIP;
 }
 
-int sa_attn_step_bwd(const void* q, const void* k, const void* v, const void* dout, const float* lse,
-                     const float* delta, float* dq, float* dk, float* dv, int32_t q_dev, int32_t kv_dev,
-                     int32_t N, int32_t layout, const sa_shape* shape, void* stream) {
+int sa_attn_step_bwd_tiled(const void* q, const void* k, const void* v, const void* dout,
+                           const float* lse, const float* delta, float* dq, float* dk, float* dv,
+                           int32_t q_dev, int32_t kv_dev, int32_t N, int32_t layout, const sa_shape* shape,
+                           int32_t skip_bq, int32_t skip_bk, void* stream) {
     if (!q || !k || !v || !dout || !lse || !delta || !dq || !dk || !dv) return SA_ERR_NULL;
     if (int e = check_shape(shape)) return e;
     if (int e = check_step(q_dev, kv_dev, N, layout)) return e;
+    if (int e = check_skip(shape, skip_bq, skip_bk)) return e;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(dout) || !aligned16(dq) ||
         !aligned16(dk) || !aligned16(dv))
         return SA_ERR_ALIGN;
-    return step_bwd(q, k, v, dout, lse, delta, dq, dk, dv, q_dev, kv_dev, layout, shape,
+    return step_bwd(q, k, v, dout, lse, delta, dq, dk, dv, q_dev, kv_dev, layout, shape, skip_bq, skip_bk,
                     (hipStream_t)stream);
 }
 
-int sa_ring_fwd(const void* Q, const void* K, const void* V, float* O, float* LSE, int32_t N,
-                int32_t layout, const sa_shape* shape, int32_t q_dev_only, float* step_ms, void* stream) {
+int sa_attn_step_bwd(const void* q, const void* k, const void* v, const void* dout, const float* lse,
+                     const float* delta, float* dq, float* dk, float* dv, int32_t q_dev, int32_t kv_dev,
+                     int32_t N, int32_t layout, const sa_shape* shape, void* stream) {
+    return sa_attn_step_bwd_tiled(q, k, v, dout, lse, delta, dq, dk, dv, q_dev, kv_dev, N, layout, shape,
+                                  0, 0, stream);
+}
+
+int sa_ring_fwd_tiled(const void* Q, const void* K, const void* V, float* O, float* LSE, int32_t N,
+                      int32_t layout, const sa_shape* shape, int32_t skip_bq, int32_t skip_bk,
+                      int32_t q_dev_only, float* step_ms, void* stream) {
     if (!Q || !K || !V || !O || !LSE) return SA_ERR_NULL;
     if (int e = check_shape(shape)) return e;
+    if (int e = check_skip(shape, skip_bq, skip_bk)) return e;
     if (N < 1 || q_dev_only >= N) return SA_ERR_DEV;
     if (layout != SA_CONTIGUOUS && layout != SA_STRIPED) return SA_ERR_LAYOUT;
     if (shape->stride_h < (int64_t)N * shape->c * shape->d || shape->stat_stride_h < (int64_t)N * shape->c)
@@ -206,7 +236,7 @@ int sa_ring_fwd(const void* Q, const void* K, const void* V, float* O, float* LS
             const int k = ((j - i) % N + N) % N;            // Algorithm 1: block held in round i
             if (!timer.begin(st, i * N + j)) return SA_ERR_HIP;
             int e = step_fwd(in_at(Q, j), in_at(K, k), in_at(V, k), O + j * shard,
-                             LSE + (int64_t)j * shape->c, j, k, layout, shape, st);
+                             LSE + (int64_t)j * shape->c, j, k, layout, shape, skip_bq, skip_bk, st);
             if (e) return e;
             if (!timer.end(st)) return SA_ERR_HIP;
         }
@@ -214,11 +244,18 @@ int sa_ring_fwd(const void* Q, const void* K, const void* V, float* O, float* LS
     return timer.collect(st, step_ms) ? SA_OK : SA_ERR_HIP;
 }
 
-int sa_ring_bwd(const void* Q, const void* K, const void* V, const void* dO, const float* O,
-                const float* LSE, float* delta, float* dQ, float* dK, float* dV, int32_t N, int32_t layout,
-                const sa_shape* shape, int32_t q_dev_only, float* step_ms, void* stream) {
+int sa_ring_fwd(const void* Q, const void* K, const void* V, float* O, float* LSE, int32_t N,
+                int32_t layout, const sa_shape* shape, int32_t q_dev_only, float* step_ms, void* stream) {
+    return sa_ring_fwd_tiled(Q, K, V, O, LSE, N, layout, shape, 0, 0, q_dev_only, step_ms, stream);
+}
+
+int sa_ring_bwd_tiled(const void* Q, const void* K, const void* V, const void* dO, const float* O,
+                      const float* LSE, float* delta, float* dQ, float* dK, float* dV, int32_t N,
+                      int32_t layout, const sa_shape* shape, int32_t skip_bq, int32_t skip_bk,
+                      int32_t q_dev_only, float* step_ms, void* stream) {
     if (!Q || !K || !V || !dO || !O || !LSE || !delta || !dQ || !dK || !dV) return SA_ERR_NULL;
     if (int e = check_shape(shape)) return e;
+    if (int e = check_skip(shape, skip_bq, skip_bk)) return e;
     if (N < 1 || q_dev_only >= N) return SA_ERR_DEV;
     if (layout != SA_CONTIGUOUS && layout != SA_STRIPED) return SA_ERR_LAYOUT;
     if (shape->stride_h < (int64_t)N * shape->c * shape->d || shape->stat_stride_h < (int64_t)N * shape->c)
@@ -249,12 +286,19 @@ int sa_ring_bwd(const void* Q, const void* K, const void* V, const void* dO, con
             if (!timer.begin(st, i * N + j)) return SA_ERR_HIP;
             int e = step_bwd(in_at(Q, j), in_at(K, k), in_at(V, k), in_at(dO, j),
                              LSE + (int64_t)j * shape->c, delta + (int64_t)j * shape->c, dQ + j * shard,
-                             dK + k * shard, dV + k * shard, j, k, layout, shape, st);
+                             dK + k * shard, dV + k * shard, j, k, layout, shape, skip_bq, skip_bk, st);
             if (e) return e;
             if (!timer.end(st)) return SA_ERR_HIP;
         }
     }
     return timer.collect(st, step_ms) ? SA_OK : SA_ERR_HIP;
+}
+
+int sa_ring_bwd(const void* Q, const void* K, const void* V, const void* dO, const float* O,
+                const float* LSE, float* delta, float* dQ, float* dK, float* dV, int32_t N, int32_t layout,
+                const sa_shape* shape, int32_t q_dev_only, float* step_ms, void* stream) {
+    return sa_ring_bwd_tiled(Q, K, V, dO, O, LSE, delta, dQ, dK, dV, N, layout, shape, 0, 0, q_dev_only,
+                             step_ms, stream);
 }
 
 int sa_step_mask(int32_t q_dev, int32_t kv_dev, int32_t N, int32_t layout, int32_t* kind, int32_t* off) {
@@ -274,6 +318,27 @@ int64_t sa_step_pairs(int32_t q_dev, int32_t kv_dev, int32_t N, int32_t layout, 
     if (kind == sa::MASK_EMPTY) return 0;
     if (kind == sa::MASK_FULL) return c * c;
     return off ? c * (c - 1) / 2 : c * (c + 1) / 2;
+}
+
+int sa_step_tiles(int32_t q_dev, int32_t kv_dev, int32_t N, int32_t layout, int64_t c, int64_t skip_bq,
+                  int64_t skip_bk, int64_t* computed, int64_t* total) {
+    if (!computed || !total) return SA_ERR_NULL;
+    if (int e = check_step(q_dev, kv_dev, N, layout)) return e;
+    if (c < 1 || skip_bq < 1 || skip_bk < 1 || c % skip_bq || c % skip_bk) return SA_ERR_SHAPE;
+    int kind, off;
+    classify(q_dev, kv_dev, layout, &kind, &off);
+    const int64_t nq = c / skip_bq, nk = c / skip_bk;
+    *total = nq * nk;
+    if (kind == sa::MASK_EMPTY) { *computed = 0; return SA_OK; }
+    if (kind == sa::MASK_FULL) { *computed = nq * nk; return SA_OK; }
+    // tile (r, s) holds an allowed pair iff its first key s*bk <= its last query (r+1)*bq - 1 - off
+    int64_t n = 0;
+    for (int64_t r = 0; r < nq; ++r) {
+        const int64_t last = (r + 1) * skip_bq - 1 - off;       // last key any query of the tile sees
+        if (last >= 0) n += (last / skip_bk + 1 < nk) ? last / skip_bk + 1 : nk;
+    }
+    *computed = n;
+    return SA_OK;
 }
 
 const char* sa_status_str(int status) {

@@ -120,7 +120,12 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
     const int q0 = qt * BM, a = q0 + 32 * wave + n;
     // all four wavefronts walk the 2 n_kt sub-tiles of the workgroup (at most three are
     // entirely masked for a wavefront); the element mask runs on the last four only
-    const int n_kt = TRI ? (q0 + BM) / DT_ROWS : p.c / DT_ROWS;
+    const int n_kt_fine = TRI ? (q0 + BM) / DT_ROWS : p.c / DT_ROWS;
+    int n_kt = n_kt_fine;
+    if (TRI && p.skip_bq > 0) {       // emulated coarse skipping, as in the forward kernel
+        const int q_hi = (q0 / p.skip_bq + 1) * p.skip_bq - 1;
+        n_kt = min(p.c, ((q_hi - p.off) / p.skip_bk + 1) * p.skip_bk) / DT_ROWS;
+    }
     const int mask_base = a - p.off - 4 * h;     // sub-tile v: allowed iff 8 (r/4) + r%4 <= mask_base - 32 v
 
     uint32_t arow[8], tr0[4], tr1[4], gl[4];
@@ -192,10 +197,15 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
     using P1 = std::integral_constant<int, 1>;
     int t = 0;
     if (TRI) {
-        // trips 0 .. n_kt - 3 without the element mask, then two masked trips (n_kt is even)
-        for (; t + 2 < n_kt; t += 2) {
+        // trips before the diagonal without the element mask, then masked trips: two, more
+        // under emulated coarse skipping (n_kt_fine and n_kt are even)
+        for (; t + 2 < n_kt_fine; t += 2) {
             trip(F{}, F{}, P0{}, t);
             trip(F{}, F{}, P1{}, t + 1);
+        }
+        for (; t + 2 < n_kt; t += 2) {
+            trip(F{}, T{}, P0{}, t);
+            trip(F{}, T{}, P1{}, t + 1);
         }
         trip(F{}, T{}, P0{}, t);
         trip(T{}, T{}, P1{}, t + 1);
@@ -345,7 +355,11 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
     const int n_qt = p.c / DT_ROWS;
     // query tiles holding at least one allowed pair (query a >= key + off): from tile k0 / 64
     // on; only its first four 32-query sub-tiles can cross the diagonal for some wavefront
-    const int t_first = TRI ? k0 / DT_ROWS : 0;
+    const int t_first_fine = TRI ? k0 / DT_ROWS : 0;
+    int t_first = t_first_fine;
+    if (TRI && p.skip_bq > 0)   // emulated coarse skipping: from the first skip_bq-tall query tile
+                                // that shares an allowed pair with these keys' skip_bk-wide tile
+        t_first = ((k0 / p.skip_bk * p.skip_bk + p.off) / p.skip_bq) * p.skip_bq / DT_ROWS;
     // sub-tile u: register r (query 32 u + 8 (r/4) + 4h + r%4) is allowed iff
     // 8 (r/4) + r%4 >= mask_base - 32 u
     const int mask_base = key + p.off - 4 * h;
@@ -442,11 +456,14 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
     // t_first and n_qt are even (c and k0 are multiples of 128): trips come in pairs and the
     // last one has odd parity
     int t = t_first;
-    if (TRI) {                                   // the first two trips carry the element mask
-        trip(T{}, P0{}, F{}, t);
-        if (t + 2 < n_qt) trip(T{}, P1{}, F{}, t + 1);
-        else trip(T{}, P1{}, T{}, t + 1);
-        t += 2;
+    if (TRI) {
+        // the trips up to the diagonal carry the element mask: the first two, more under
+        // emulated coarse skipping
+        for (; t < t_first_fine + 2; t += 2) {
+            trip(T{}, P0{}, F{}, t);
+            if (t + 2 < n_qt) trip(T{}, P1{}, F{}, t + 1);
+            else trip(T{}, P1{}, T{}, t + 1);
+        }
     }
     for (; t + 2 < n_qt; t += 2) {
         trip(F{}, P0{}, F{}, t);

@@ -73,6 +73,12 @@ __device__ inline void load_tile_direct(dt_rsrc matrix, int tile_byte_offset, ch
     for (int j = 0; j < LPW; ++j) dt_load_piece(matrix, tile_byte_offset, g[j], lds_tile + (LPW * wave + j) * 1024);
 }
 
+__device__ inline void load_v_tile_direct(dt_rsrc matrix, int tile_byte_offset, char* lds_tile, uint32_t g0, int wave) {
+#pragma unroll
+    for (int j = 0; j < LPW; ++j)
+        dt_load_piece(matrix, tile_byte_offset + j * 1024, g0, lds_tile + (LPW * wave + j) * 1024);
+}
+
 __device__ inline bf16x8 lds_read_b128(const char* lds, uint32_t addr) {
     return *reinterpret_cast<const bf16x8*>(lds + addr);
 }
@@ -185,7 +191,14 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     // b <= a - off, i.e. tiles 0 .. (q0 + 127) / 64.  All four wavefronts walk all 2 n_kt
     // sub-tiles (at most NW - 1 of them are entirely masked for a wavefront); the element
     // mask is applied on the last NW sub-tiles only.
-    const int n_kt = TRI ? (q0 + BM) / TILE_ROWS : p.c / TILE_ROWS;
+    const int n_kt_fine = TRI ? (q0 + BM) / TILE_ROWS : p.c / TILE_ROWS;
+    int n_kt = n_kt_fine;
+    if (TRI && p.skip_bq > 0) {
+        // emulated coarse skipping: up to the last skip_bk-wide key tile that shares an allowed
+        // pair with the skip_bq-tall tile these queries belong to
+        const int q_hi = (q0 / p.skip_bq + 1) * p.skip_bq - 1;
+        n_kt = min(p.c, ((q_hi - p.off) / p.skip_bk + 1) * p.skip_bk) / TILE_ROWS;
+    }
     // sub-tile v: register r (key 32 v + 8 (r/4) + 4h + r%4) is allowed iff
     // 8 (r/4) + r%4 <= mask_base - 32 v
     const int mask_base = a - p.off - 4 * h;
@@ -193,7 +206,7 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     // per-lane addresses: K A-operand reads per k-step, V transposing reads per 32-column
     // block (bytes within a 32-row half tile), and the global byte offsets of this lane's
     // direct loads
-    uint32_t kaddr[8], vaddr[4], kg[4], vg[4];
+    uint32_t kaddr[8], vaddr[4], kg[4], vg0;
     {
         const int x = n & 15;
 #pragma unroll
@@ -207,13 +220,15 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
         for (int j = 0; j < 4; ++j) {
             const int r = 4 * LPW * wave + 4 * j + lr;     // tile row this lane fills with load j
             kg[j] = r * 256 + ((pc ^ (r & 15)) << 4);
-            vg[j] = r * 256 + ((pc ^ (lr << 2)) << 4);
         }
+        // V's swizzle depends on the row within the 4-row group only, so its four pieces
+        // differ by exactly 1 KiB: one lane offset, the rest goes into the scalar offset
+        vg0 = (4 * LPW * wave + lr) * 256 + ((pc ^ (lr << 2)) << 4);
     }
 
     // first tiles on their way while the running state is loaded
     load_tile_direct(K, 0, k_lds0, kg, wave);
-    load_tile_direct(V, 0, v_lds0, vg, wave);
+    load_v_tile_direct(V, 0, v_lds0, vg0, wave);
     load_tile_direct(K, TILE_BYTES, k_lds1, kg, wave);     // n_kt >= 2 always
 
     bf16x8 qf[8];
@@ -255,9 +270,10 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     //              requested at barrier t-1, have landed
     //   u = 2t+1: QK(2t+2): K tile t+1, first half     PV(2t): V tile t, first half
     // PAR = t & 1 fixes every LDS offset at compile time.
-    auto trip = [&](auto first_c, auto last_c, auto mask_c, auto par_c, int t) __attribute__((always_inline)) {
+    // HOT: a trip of the hot loop, where tiles t + 1 and t + 2 always exist
+    auto trip = [&](auto first_c, auto last_c, auto mask_c, auto par_c, int t, auto hot_c) __attribute__((always_inline)) {
         constexpr bool FIRST = decltype(first_c)::value, LAST = decltype(last_c)::value;
-        constexpr bool MASK = decltype(mask_c)::value;
+        constexpr bool MASK = decltype(mask_c)::value, HOT = decltype(hot_c)::value;
         constexpr int PAR = decltype(par_c)::value;
         char* const k_cur = PAR ? k_lds1 : k_lds0;
         char* const k_nxt = PAR ? k_lds0 : k_lds1;
@@ -267,8 +283,8 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
                                        k_cur + TILE_BYTES / 2, v_prv + TILE_BYTES / 2, mask_base - 64 * t);
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-        if (t + 2 < n_kt) load_tile_direct(K, (t + 2) * TILE_BYTES, k_cur, kg, wave);
-        if (t + 1 < n_kt) load_tile_direct(V, (t + 1) * TILE_BYTES, v_prv, vg, wave);
+        if (HOT || t + 2 < n_kt) load_tile_direct(K, (t + 2) * TILE_BYTES, k_cur, kg, wave);
+        if (HOT || t + 1 < n_kt) load_v_tile_direct(V, (t + 1) * TILE_BYTES, v_prv, vg0, wave);
         step<!LAST, true, true, MASK>(s_b, s_a, p_b, p_a, oacc, qf, m, l, kappa, kaddr, vaddr, k_nxt, v_cur,
                                       mask_base - 64 * t - 32);
     };
@@ -281,29 +297,41 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     auto run = [&](auto mask_c, int t) __attribute__((always_inline)) {
         const bool last = t + 1 == n_kt;
         if (t & 1) {
-            if (last) trip(F{}, T{}, mask_c, P1{}, t);
-            else trip(F{}, F{}, mask_c, P1{}, t);
+            if (last) trip(F{}, T{}, mask_c, P1{}, t, F{});
+            else trip(F{}, F{}, mask_c, P1{}, t, F{});
         } else if (t == 0) {
-            trip(T{}, F{}, mask_c, P0{}, t);
+            trip(T{}, F{}, mask_c, P0{}, t, F{});
         } else if (last) {
-            trip(F{}, T{}, mask_c, P0{}, t);
+            trip(F{}, T{}, mask_c, P0{}, t, F{});
         } else {
-            trip(F{}, F{}, mask_c, P0{}, t);
+            trip(F{}, F{}, mask_c, P0{}, t, F{});
         }
     };
-    // triangular steps: the last BM / 64 trips carry the element mask
-    const int t_mask = TRI ? n_kt - BM / TILE_ROWS : n_kt;
+    // triangular steps: the trips from the diagonal on carry the element mask (the last
+    // BM / 64 ones, more under emulated coarse skipping)
+    const int t_mask = TRI ? n_kt_fine - BM / TILE_ROWS : n_kt;
     const int t_hot = TRI ? t_mask : n_kt - 1;       // plain, neither first nor last: [1, t_hot)
     int t = 0;
     if (t_mask > 0) {
         run(F{}, 0);
         for (t = 1; t + 1 < t_hot; t += 2) {          // the hot loop: two plain trips per turn
-            trip(F{}, F{}, F{}, P1{}, t);
-            trip(F{}, F{}, F{}, P0{}, t + 1);
+            trip(F{}, F{}, F{}, P1{}, t, T{});         // t + 3 < t_hot + 2 <= n_kt
+            trip(F{}, F{}, F{}, P0{}, t + 1, T{});
         }
         for (; t < t_mask; ++t) run(F{}, t);
     }
-    for (; t < n_kt; ++t) run(T{}, t);
+    // masked trips; under emulated coarse skipping there are many, so pairs of them that are
+    // neither first nor last take the same fixed-parity form as the hot loop
+    if (TRI)
+        for (; t < n_kt; ++t) {
+            if (!(t & 1) && t > 0 && t + 3 < n_kt) {
+                trip(F{}, F{}, T{}, P0{}, t, T{});
+                trip(F{}, F{}, T{}, P1{}, t + 1, T{});
+                ++t;
+            } else {
+                run(T{}, t);
+            }
+        }
     // final iteration u = 2 n_kt: PV(2 n_kt - 1): V tile n_kt - 1, second half; P in p_b
     {
         const char* v_last = (((n_kt - 1) & 1) ? v_lds1 : v_lds0) + TILE_BYTES / 2;

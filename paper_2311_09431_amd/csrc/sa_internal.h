@@ -28,6 +28,11 @@ struct StepArgs {
     float scale;
     int kind;             // MaskKind (never MASK_EMPTY at launch)
     int off;              // 0 or 1 when kind == MASK_TRI
+    // Emulated tile-skipping granularity (Sec. 3.1), MFMA kernels only: 0 = the kernel's own
+    // (32 x 32); otherwise every sub-tile of a skip_bq x skip_bk tile of the block that holds
+    // at least one allowed pair is computed (masked elements contribute exact zeros).
+    // Both are multiples of 128 that divide c.
+    int skip_bq, skip_bk;
 };
 
 // launchers: return hipSuccess or the launch error

@@ -36,3 +36,37 @@ def attention_only_limit(N, c=None):
     if c is None:
         return (2 * N - 1) / N
     return (c * (c + 1) / 2 + (N - 1) * c * c) / (N * c * (c + 1) / 2)
+
+
+def computed_tiles(q_dev, kv_dev, c, striped, tile_q, tile_k):
+    """Tiles of the step's c x c block that hold at least one allowed pair, i.e. are computed
+    when work is skipped per tile_q x tile_k tile (Sec. 2.2.1, 3.1).  Allowed pairs in local
+    indices: key b <= query a - off (Sec. 2.2, 2.3)."""
+    nq, nk = c // tile_q, c // tile_k
+    if striped:
+        off = 1 if kv_dev > q_dev else 0
+    elif q_dev < kv_dev:
+        return 0
+    elif q_dev > kv_dev:
+        return nq * nk
+    else:
+        off = 0
+    n = 0
+    for r in range(nq):
+        last_key = (r + 1) * tile_q - 1 - off
+        if last_key >= 0:
+            n += min(nk, last_key // tile_k + 1)
+    return n
+
+
+def tiled_attention_limit(N, c, tile_q, tile_k, devices=None):
+    """attention_only_limit when work is skipped per tile_q x tile_k tile: per-round worst-device
+    number of computed tiles summed over the ring, contiguous over striped.  1.0 means striping
+    gains nothing at that granularity (Sec. 3.2: c = 4096 with 2048 x 4096 tiles).  `devices`
+    restricts the maximum to those query devices (default: all N)."""
+    devs = range(N) if devices is None else devices
+
+    def ring_sum(striped):
+        return sum(max(computed_tiles(j, (j - i) % N, c, striped, tile_q, tile_k) for j in devs)
+                   for i in range(N))
+    return ring_sum(False) / ring_sum(True)

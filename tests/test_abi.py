@@ -121,3 +121,37 @@ def test_header_is_valid_c():
     r = subprocess.run([gcc, "-std=c99", "-Wall", "-Werror", "-fsyntax-only", "-x", "c", "-I",
                         os.path.join(ROOT, "include"), "-"], input=src, text=True, capture_output=True)
     assert r.returncode == 0, r.stderr
+
+
+@pytest.mark.parametrize("N,c,bq,bk", [(4, 16, 4, 8), (4, 16, 8, 4), (2, 12, 3, 4), (3, 8, 8, 8), (2, 8, 1, 1)])
+def test_step_tiles_match_the_oracle_classifier(N, c, bq, bk):
+    for layout in (sa.CONTIGUOUS, sa.STRIPED):
+        for j in range(N):
+            for k in range(N):
+                full, part, empty = orc.classify_tiles(orc.get_mask(j, k, N, c, layout), bq, bk)
+                assert sa.sa_step_tiles(j, k, N, layout, c, bq, bk) == (full + part, full + part + empty)
+
+
+def test_step_tiles_reproduce_the_printed_skipping_figures():
+    # tests/golden/tiling_examples.txt: the fractions of tiles the paper says are skipped
+    with open(os.path.join(ROOT, "tests", "golden", "tiling_examples.txt")) as f:
+        rows = [l.split("#")[0].split() for l in f if l.split("#")[0].strip()]
+    assert rows
+    for c, tq, tk, mask, _full, _part, empty, pct in rows:
+        c, tq, tk, empty, pct = int(c), int(tq), int(tk), int(empty), int(pct)
+        # "causal" = a diagonal block (either layout with kv_dev <= q_dev); "striped_lo" = a
+        # striped step with kv_dev > q_dev
+        j, k = (1, 1) if mask == "causal" else (0, 1)
+        computed, total = sa.sa_step_tiles(j, k, 2, sa.STRIPED, c, tq, tk)
+        assert total - computed == empty
+        assert round(100 * (total - computed) / total) == pct
+
+
+def test_step_tiles_errors():
+    L = sa.lib()
+    a, b = ctypes.c_int64(), ctypes.c_int64()
+    assert L.sa_step_tiles(0, 0, 2, 1, 8, 3, 4, ctypes.byref(a), ctypes.byref(b)) == -2
+    assert L.sa_step_tiles(0, 0, 2, 1, 8, 0, 4, ctypes.byref(a), ctypes.byref(b)) == -2
+    assert L.sa_step_tiles(0, 5, 2, 1, 8, 4, 4, ctypes.byref(a), ctypes.byref(b)) == -3
+    assert L.sa_step_tiles(0, 0, 2, 7, 8, 4, 4, ctypes.byref(a), ctypes.byref(b)) == -5
+    assert L.sa_step_tiles(0, 0, 2, 1, 8, 4, 4, None, ctypes.byref(b)) == -1

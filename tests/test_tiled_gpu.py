@@ -1,0 +1,101 @@
+"""Emulated tile-skipping granularity (Sec. 3.1, 3.2): the *_tiled entry points do more work
+(every sub-tile of a coarse tile that holds an allowed pair) but must give the SAME bits as
+the plain entry points, because masked elements contribute exact zeros; and the plain entry
+points are checked against the oracle elsewhere.  One case is also set beside the oracle
+directly."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2311_09431_amd import binding as sa
+from paper_2311_09431_amd import inputs
+from tests import helpers as hp
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    # S, N, skip_bq, skip_bk            c
+    (2048, 2, 256, 512),              # 1024
+    (2048, 2, 512, 256),
+    (2048, 2, 1024, 1024),            # one tile: nothing can be skipped
+    (2048, 2, 128, 128),              # the finest the emulation takes
+    (2048, 2, 256, 1024),             # the paper's GPU tile shape (tall / 2 x full width)
+    (1152, 3, 128, 384),              # c = 384: odd tile counts
+    (1152, 3, 384, 128),
+    (4096, 4, 512, 512),              # c = 1024, four devices
+]
+
+
+def _ring_fwd(Qp, Kp, Vp, N, layout, c, bq, bk):
+    B, H, S, d = Qp.shape
+    O = torch.empty(B, H, S, d, dtype=torch.float32, device=Qp.device)
+    LSE = torch.empty(B, H, S, dtype=torch.float32, device=Qp.device)
+    shape = sa.shard_shape(Qp, c, LSE)
+    if bq:
+        sa.sa_ring_fwd_tiled(Qp, Kp, Vp, O, LSE, N, layout, shape, bq, bk)
+    else:
+        sa.sa_ring_fwd(Qp, Kp, Vp, O, LSE, N, layout, shape)
+    return O, LSE, shape
+
+
+@pytest.mark.parametrize("layout", [sa.CONTIGUOUS, sa.STRIPED])
+@pytest.mark.parametrize("S,N,bq,bk", CASES)
+def test_tiled_ring_gives_the_same_bits(layout, S, N, bq, bk):
+    B, H, d = 1, 2, 128
+    c = S // N
+    Q, K, V, dO = (x.cuda() for x in inputs.qkv(B, H, S, d, S + bq + bk, torch.bfloat16, with_dout=True))
+    Qp, Kp, Vp, dOp = (hp.to_device_order(x, N, layout) for x in (Q, K, V, dO))
+    O0, L0, shape = _ring_fwd(Qp, Kp, Vp, N, layout, c, 0, 0)
+    O1, L1, _ = _ring_fwd(Qp, Kp, Vp, N, layout, c, bq, bk)
+    torch.cuda.synchronize()
+    assert torch.equal(O0, O1) and torch.equal(L0, L1)
+    delta = torch.empty_like(L0)
+    g0 = [torch.empty_like(O0) for _ in range(3)]
+    g1 = [torch.empty_like(O0) for _ in range(3)]
+    sa.sa_ring_bwd(Qp, Kp, Vp, dOp, O0, L0, delta, *g0, N, layout, shape)
+    sa.sa_ring_bwd_tiled(Qp, Kp, Vp, dOp, O0, L0, delta, *g1, N, layout, shape, bq, bk)
+    torch.cuda.synchronize()
+    for x, y in zip(g0, g1):
+        assert torch.equal(x, y)
+
+
+@pytest.mark.parametrize("layout", [sa.CONTIGUOUS, sa.STRIPED])
+def test_tiled_single_steps_against_the_oracle(layout):
+    # step-by-step through the tiled step entry points, then the usual oracle comparison
+    B, H, S, d, N, bq, bk = 1, 1, 1024, 128, 2, 256, 512
+    c = S // N
+    Q, K, V = (x.cuda() for x in inputs.qkv(B, H, S, d, 91, torch.bfloat16))
+    Qp, Kp, Vp = (hp.to_device_order(x, N, layout) for x in (Q, K, V))
+    O = torch.empty(B, H, S, d, dtype=torch.float32, device="cuda")
+    LSE = torch.empty(B, H, S, dtype=torch.float32, device="cuda")
+    shape = sa.shard_shape(Qp, c, LSE)
+    for j in range(N):
+        sa.sa_state_init(O[:, :, j * c:], LSE[:, :, j * c:], shape)
+    for j in range(N):
+        for k in range(N):
+            sa.sa_attn_step_fwd_tiled(Qp[:, :, j * c:], Kp[:, :, k * c:], Vp[:, :, k * c:],
+                                      O[:, :, j * c:], LSE[:, :, j * c:], j, k, N, layout, shape, bq, bk)
+    torch.cuda.synchronize()
+    Oref, Lref = hp.oracle_forward(Q, K, V, 1.0 / np.sqrt(d))
+    Oh = hp.from_device_order_host(O.cpu().numpy(), N, layout)
+    Lh = hp.from_device_order_host(LSE.cpu().numpy(), N, layout)
+    assert hp.max_abs_err(Oh, Oref) <= 2e-2
+    assert hp.max_abs_err(Lh, Lref) <= 1e-3
+
+
+def test_tiled_arguments_are_validated():
+    B, H, S, d, N = 1, 1, 512, 128, 2
+    c = S // N
+    Q, K, V = (x.cuda() for x in inputs.qkv(B, H, S, d, 3, torch.bfloat16))
+    O = torch.zeros(B, H, S, d, dtype=torch.float32, device="cuda")
+    LSE = torch.zeros(B, H, S, dtype=torch.float32, device="cuda")
+    shape = sa.shard_shape(Q, c, LSE)
+    for bq, bk in [(64, 128), (128, 192), (128, 0), (0, 128), (512, 128), (-128, 128)]:
+        with pytest.raises(sa.StripedAttnError) as e:
+            sa.sa_ring_fwd_tiled(Q, K, V, O, LSE, N, sa.STRIPED, shape, bq, bk)
+        assert e.value.status == -2
+    # a shape the matrix-core kernels do not take has no emulation
+    Q32 = Q.float()
+    with pytest.raises(sa.StripedAttnError) as e:
+        sa.sa_ring_fwd_tiled(Q32, Q32, Q32, O, LSE, N, sa.STRIPED, sa.shard_shape(Q32, c, LSE), 128, 128)
+    assert e.value.status == -2
