@@ -47,7 +47,8 @@ typedef enum { SA_F32 = 0, SA_BF16 = 1 } sa_dtype;
 typedef struct {
     int32_t B, H;          /* batch, heads */
     int32_t c;             /* rows per device (block size) */
-    int32_t d;             /* head dimension: any 1..256 (multiple of 4 for fp32, 8 for bf16);
+    int32_t d;             /* head dimension: any multiple of 4 up to 256 (Table 1's
+                              models have 128 and 100);
                               bf16 with d = 128 and c % 128 == 0 takes the MFMA kernels */
     int64_t stride_b;      /* elements between batches in Q/K/V/dO/O/dQ/dK/dV */
     int64_t stride_h;      /* elements between heads in the same tensors */

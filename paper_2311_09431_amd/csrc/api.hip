@@ -17,7 +17,7 @@ int check_shape(const sa_shape* s) {
     if (s->dtype != SA_F32 && s->dtype != SA_BF16) return SA_ERR_DTYPE;
     if (s->B < 1 || s->H < 1 || s->c < 1 || s->d < 1 || s->d > 256) return SA_ERR_SHAPE;
     if ((int64_t)s->B * s->H > 65535) return SA_ERR_SHAPE;
-    const int dmul = (s->dtype == SA_F32) ? 4 : 8;
+    const int dmul = 4;      // rows are read four elements at a time (16 or 8 bytes)
     if (s->d % dmul) return SA_ERR_SHAPE;
     if (s->stride_h < (int64_t)s->c * s->d || s->stat_stride_h < s->c) return SA_ERR_SHAPE;
     if (s->B > 1 && (s->stride_b < s->stride_h || s->stat_stride_b < s->stat_stride_h))

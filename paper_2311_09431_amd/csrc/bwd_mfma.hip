@@ -495,7 +495,9 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
 bool bwd_mfma_supported(const StepArgs& a, int dtype) {
     // c <= 2^22 rows: a shard matrix (256 bytes per row) stays inside a buffer descriptor's
     // 32-bit byte range with room to spare
-    return dtype == SA_BF16 && a.d == D && a.c % BM == 0 && a.c <= (1 << 22);
+    // ... and 16-byte aligned rows for every (batch, head)
+    return dtype == SA_BF16 && a.d == D && a.c % BM == 0 && a.c <= (1 << 22) && a.stride_b % 8 == 0 &&
+           a.stride_h % 8 == 0;
 }
 
 hipError_t launch_bwd_mfma(const StepArgs& a, hipStream_t st) {

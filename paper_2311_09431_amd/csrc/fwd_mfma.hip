@@ -61,7 +61,6 @@ constexpr int TILE_BYTES = TILE_ROWS * D * 2;   // 16 KiB
 constexpr float RESCALE_LOG2 = 8.f;
 
 typedef __attribute__((address_space(3))) char lds_char;
-typedef __attribute__((address_space(1))) const char global_char;
 typedef lds_s16x4_t lds_s16x4;
 
 // One tile (64 rows) of K or V: 16 KiB = 16 wavefront loads of 1 KiB, 4 per wavefront.
@@ -358,7 +357,9 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
 bool fwd_mfma_supported(const StepArgs& a, int dtype) {
     // c <= 2^22 rows: a shard matrix (256 bytes per row) stays inside a buffer descriptor's
     // 32-bit byte range with room to spare
-    return dtype == SA_BF16 && a.d == D && a.c % BM == 0 && a.c <= (1 << 22);
+    // ... and 16-byte aligned rows for every (batch, head)
+    return dtype == SA_BF16 && a.d == D && a.c % BM == 0 && a.c <= (1 << 22) && a.stride_b % 8 == 0 &&
+           a.stride_h % 8 == 0;
 }
 
 hipError_t launch_fwd_mfma(const StepArgs& a, hipStream_t st) {

@@ -70,7 +70,7 @@ def test_argument_errors_are_reported_before_any_launch():
     assert f(p, p, p, p, p, 0, 0, 4, 0, ctypes.byref(_shape(d=66)), None) == -2
     assert f(p, p, p, p, p, 0, 0, 4, 0, ctypes.byref(_shape(c=0)), None) == -2
     assert f(p, p, p, p, p, 0, 0, 4, 0, ctypes.byref(_shape(stride_h=10)), None) == -2
-    assert f(p, p, p, p, p, 0, 0, 4, 0, ctypes.byref(_shape(dtype=sa.BF16, stride_h=256 * 64 + 4)),
+    assert f(p, p, p, p, p, 0, 0, 4, 0, ctypes.byref(_shape(dtype=sa.BF16, stride_h=256 * 64 + 2)),
              None) == -6
     # an entirely masked contiguous step is a no-op that succeeds without a launch
     assert f(p, p, p, p, p, 0, 1, 4, sa.CONTIGUOUS, ctypes.byref(ok), None) == 0

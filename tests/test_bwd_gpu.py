@@ -38,6 +38,7 @@ def _check(B, H, S, d, N, layout, dtype, seed, use_driver=False):
     (1, 1, 8, 4, 8, torch.float32),        # c = 1
     (1, 2, 192, 64, 4, torch.bfloat16),
     (1, 2, 96, 128, 4, torch.bfloat16),
+    (1, 2, 128, 100, 4, torch.bfloat16),   # head dimension of Table 1's 3B model
 ])
 def test_generic_backward(layout, B, H, S, d, N, dtype):
     _check(B, H, S, d, N, layout, dtype, seed=S + d + 1)

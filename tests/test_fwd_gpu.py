@@ -45,6 +45,7 @@ def test_tiny_fp32_config(layout):
     (1, 2, 256, 256, 4, torch.float32),    # largest head dimension
     (2, 2, 192, 64, 4, torch.bfloat16),    # bf16 storage on the generic path
     (1, 2, 96, 128, 4, torch.bfloat16),    # d = 128 but c = 24: not MFMA-eligible
+    (1, 2, 256, 100, 4, torch.bfloat16),   # head dimension of Table 1's 3B model (3200 / 32)
 ])
 def test_generic_shapes(layout, B, H, S, d, N, dtype):
     _check_ring(B, H, S, d, N, layout, dtype, seed=S + d)
