@@ -54,6 +54,9 @@ WORKLOADS = {
     "cfg5": dict(B=1, H=8, d=128, S=786432, N=16, q_dev=15,
                  desc="one device's share at 786k: B1 H8 d128 S786432 N16 (49152-token shards), bf16, "
                       "q_dev 15"),
+    "3b": dict(B=1, H=32, d=100, S=262144, N=8, q_dev=7,
+               desc="cfg3 with the head dimension of Table 1's 3B model: B1 H32 d100 S262144 N8, bf16, "
+                    "q_dev 7 (matrix-core kernels, columns zero-padded to 128)"),
     "tiny": dict(B=1, H=2, d=128, S=4096, N=4, q_dev=-1, desc="B1 H2 d128 S4096 N4, bf16 (quick check)"),
 }
 

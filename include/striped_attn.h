@@ -49,7 +49,8 @@ typedef struct {
     int32_t c;             /* rows per device (block size) */
     int32_t d;             /* head dimension: any multiple of 4 up to 256 (Table 1's
                               models have 128 and 100);
-                              bf16 with d = 128 and c % 128 == 0 takes the MFMA kernels */
+                              bf16 with d <= 128 and c % 128 == 0 takes the MFMA kernels
+                              (d < 128 zero-padded to 128 columns) */
     int64_t stride_b;      /* elements between batches in Q/K/V/dO/O/dQ/dK/dV */
     int64_t stride_h;      /* elements between heads in the same tensors */
     int64_t stat_stride_b; /* elements between batches in LSE / delta */
@@ -162,7 +163,7 @@ int sa_ring_bwd(const void* Q, const void* K, const void* V, const void* dO, con
  * if it holds none.  They exist to measure what striping gains at a given granularity, to
  * set beside the paper's tables; skip_bq = skip_bk = 0 selects the kernels' own granularity
  * (32 x 32) and is what the plain entry points do.  Otherwise both must be multiples of 128
- * that divide c, and the shape must be one the MFMA kernels take (bf16, d = 128,
+ * that divide c, and the shape must be one the MFMA kernels take (bf16, d <= 128,
  * c % 128 == 0); anything else returns SA_ERR_SHAPE.  All other arguments as in the plain
  * entry points.
  */

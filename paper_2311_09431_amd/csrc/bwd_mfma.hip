@@ -112,8 +112,10 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
     const int64_t base = b * p.stride_b + hd * p.stride_h;
     const int64_t sbase = b * p.stat_stride_b + hd * p.stat_stride_h;
     const __bf16* Q = (const __bf16*)p.q + base;
-    const dt_rsrc Kr = dt_make_rsrc((const __bf16*)p.k + base, p.c);
-    const dt_rsrc Vr = dt_make_rsrc((const __bf16*)p.v + base, p.c);
+    const int d = p.d, pitch = 2 * d;                  // d <= 128, zero-padded to 128 columns
+    const int tile_pitch = DT_ROWS * pitch;            // bytes between 64-row tiles in global memory
+    const dt_rsrc Kr = dt_make_rsrc((const __bf16*)p.k + base, p.c, pitch);
+    const dt_rsrc Vr = dt_make_rsrc((const __bf16*)p.v + base, p.c, pitch);
     const __bf16* G = (const __bf16*)p.dout + base;
     float* DQ = p.dq + base;
 
@@ -131,15 +133,15 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
     uint32_t arow[8], tr0[4], tr1[4], gl[4];
     dt_row_addrs(arow, n, h);
     dt_tr_addrs(tr0, tr1, lane);
-    dt_load_offsets(gl, lane, wave);
+    dt_load_offsets(gl, lane, wave, pitch);
     dt_load(Kr, 0, k_lds0, gl, wave);
     dt_load(Vr, 0, v_lds0, gl, wave);
-    dt_load(Kr, DT_BYTES, k_lds1, gl, wave);       // n_kt >= 2 always
-    dt_load(Vr, DT_BYTES, v_lds1, gl, wave);
+    dt_load(Kr, tile_pitch, k_lds1, gl, wave);       // n_kt >= 2 always
+    dt_load(Vr, tile_pitch, v_lds1, gl, wave);
 
     bf16x8 qf[8], gf[8];
-    load_b_frags(qf, Q + (int64_t)a * D, h);
-    load_b_frags(gf, G + (int64_t)a * D, h);
+    load_b_frags(qf, Q + (int64_t)a * d, h, d);
+    load_b_frags(gf, G + (int64_t)a * d, h, d);
     const float kappa = p.scale * LOG2E;
     float lse2 = p.lse[sbase + a] * LOG2E;
     float delta = p.delta[sbase + a];
@@ -186,8 +188,8 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
         if (!LAST) {
             __syncthreads();                    // every wavefront is done with tile t
             if (t + 2 < n_kt) {
-                dt_load(Kr, (t + 2) * DT_BYTES, k_cur, gl, wave);
-                dt_load(Vr, (t + 2) * DT_BYTES, v_cur, gl, wave);
+                dt_load(Kr, (t + 2) * tile_pitch, k_cur, gl, wave);
+                dt_load(Vr, (t + 2) * tile_pitch, v_cur, gl, wave);
             }
         }
     };
@@ -226,7 +228,9 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
     for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            float4* dst = reinterpret_cast<float4*>(DQ + (int64_t)a * D + 32 * mb + 8 * g + 4 * h);
+            const int col = 32 * mb + 8 * g + 4 * h;
+            if (col >= d) continue;                       // padding columns
+            float4* dst = reinterpret_cast<float4*>(DQ + (int64_t)a * d + col);
             float4 x = *dst;
             x.x = fmaf(p.scale, acc[mb][4 * g + 0], x.x); x.y = fmaf(p.scale, acc[mb][4 * g + 1], x.y);
             x.z = fmaf(p.scale, acc[mb][4 * g + 2], x.z); x.w = fmaf(p.scale, acc[mb][4 * g + 3], x.w);
@@ -342,8 +346,10 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
     const int b = bh / p.H, hd = bh - b * p.H;
     const int64_t base = b * p.stride_b + hd * p.stride_h;
     const int64_t sbase = b * p.stat_stride_b + hd * p.stat_stride_h;
-    const dt_rsrc Qr = dt_make_rsrc((const __bf16*)p.q + base, p.c);
-    const dt_rsrc Gr = dt_make_rsrc((const __bf16*)p.dout + base, p.c);
+    const int d = p.d, pitch = 2 * d;                  // d <= 128, zero-padded to 128 columns
+    const int tile_pitch = DT_ROWS * pitch;            // bytes between 64-row tiles in global memory
+    const dt_rsrc Qr = dt_make_rsrc((const __bf16*)p.q + base, p.c, pitch);
+    const dt_rsrc Gr = dt_make_rsrc((const __bf16*)p.dout + base, p.c, pitch);
     const __bf16* K = (const __bf16*)p.k + base;
     const __bf16* V = (const __bf16*)p.v + base;
     const float* LSE = p.lse + sbase;
@@ -367,13 +373,13 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
     uint32_t arow[8], tr0[4], tr1[4], gl[4];
     dt_row_addrs(arow, n, h);
     dt_tr_addrs(tr0, tr1, lane);
-    dt_load_offsets(gl, lane, wave);
+    dt_load_offsets(gl, lane, wave, pitch);
     // t_first and n_qt are even (k0 and c are multiples of 128): tile t_first goes to buffer 0
     // and there are always at least two tiles
-    dt_load(Qr, t_first * DT_BYTES, q_lds0, gl, wave);
-    dt_load(Gr, t_first * DT_BYTES, g_lds0, gl, wave);
-    dt_load(Qr, (t_first + 1) * DT_BYTES, q_lds1, gl, wave);
-    dt_load(Gr, (t_first + 1) * DT_BYTES, g_lds1, gl, wave);
+    dt_load(Qr, t_first * tile_pitch, q_lds0, gl, wave);
+    dt_load(Gr, t_first * tile_pitch, g_lds0, gl, wave);
+    dt_load(Qr, (t_first + 1) * tile_pitch, q_lds1, gl, wave);
+    dt_load(Gr, (t_first + 1) * tile_pitch, g_lds1, gl, wave);
     // statistics of query tile t -> stat[(t & 1)][0 | 1][64]: threads 0..63 LSE * log2(e), 64..127
     // delta.  The fetch is branch-free (wavefronts 2 and 3 re-read what 0 and 1 read and drop
     // it), so nothing waits for it before the store one trip later.
@@ -391,8 +397,8 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
     stat_store(t_first + 1, stat_fetch());
 
     bf16x8 kf[8], vf[8];
-    load_b_frags(kf, K + (int64_t)key * D, h);
-    load_b_frags(vf, V + (int64_t)key * D, h);
+    load_b_frags(kf, K + (int64_t)key * d, h, d);
+    load_b_frags(vf, V + (int64_t)key * d, h, d);
     const float kappa = p.scale * LOG2E;
     f32x16 acck[4], accv[4];
 #pragma unroll
@@ -439,8 +445,8 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
                                   mask_base - 64 * t - 32);
             __syncthreads();                     // every wavefront is done with tile t
             if (t + 2 < n_qt) {
-                dt_load(Qr, (t + 2) * DT_BYTES, q_cur, gl, wave);
-                dt_load(Gr, (t + 2) * DT_BYTES, g_cur, gl, wave);
+                dt_load(Qr, (t + 2) * tile_pitch, q_cur, gl, wave);
+                dt_load(Gr, (t + 2) * tile_pitch, g_cur, gl, wave);
                 rstat = stat_fetch();
             }
         } else {
@@ -478,7 +484,9 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
     for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            const int64_t o = (int64_t)key * D + 32 * mb + 8 * g + 4 * h;
+            const int col = 32 * mb + 8 * g + 4 * h;
+            if (col >= d) continue;                       // padding columns
+            const int64_t o = (int64_t)key * d + col;
             float4 x = *reinterpret_cast<float4*>(DV + o);
             x.x += accv[mb][4 * g + 0]; x.y += accv[mb][4 * g + 1];
             x.z += accv[mb][4 * g + 2]; x.w += accv[mb][4 * g + 3];
@@ -496,7 +504,7 @@ bool bwd_mfma_supported(const StepArgs& a, int dtype) {
     // c <= 2^22 rows: a shard matrix (256 bytes per row) stays inside a buffer descriptor's
     // 32-bit byte range with room to spare
     // ... and 16-byte aligned rows for every (batch, head)
-    return dtype == SA_BF16 && a.d == D && a.c % BM == 0 && a.c <= (1 << 22) && a.stride_b % 8 == 0 &&
+    return dtype == SA_BF16 && a.d <= D && a.d % 4 == 0 && a.c % BM == 0 && a.c <= (1 << 22) && a.stride_b % 8 == 0 &&
            a.stride_h % 8 == 0;
 }
 

@@ -72,10 +72,11 @@ __device__ inline void load_tile_direct(dt_rsrc matrix, int tile_byte_offset, ch
     for (int j = 0; j < LPW; ++j) dt_load_piece(matrix, tile_byte_offset, g[j], lds_tile + (LPW * wave + j) * 1024);
 }
 
-__device__ inline void load_v_tile_direct(dt_rsrc matrix, int tile_byte_offset, char* lds_tile, uint32_t g0, int wave) {
+__device__ inline void load_v_tile_direct(dt_rsrc matrix, int tile_byte_offset, char* lds_tile, uint32_t g0, int wave,
+                                          int pitch) {
 #pragma unroll
-    for (int j = 0; j < LPW; ++j)
-        dt_load_piece(matrix, tile_byte_offset + j * 1024, g0, lds_tile + (LPW * wave + j) * 1024);
+    for (int j = 0; j < LPW; ++j)     // piece j: four rows further down
+        dt_load_piece(matrix, tile_byte_offset + j * 4 * pitch, g0, lds_tile + (LPW * wave + j) * 1024);
 }
 
 __device__ inline bf16x8 lds_read_b128(const char* lds, uint32_t addr) {
@@ -179,8 +180,10 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     const int b = bh / p.H, hd = bh - b * p.H;
     const int64_t base = b * p.stride_b + hd * p.stride_h;
     const __bf16* Q = (const __bf16*)p.q + base;
-    const dt_rsrc K = dt_make_rsrc((const __bf16*)p.k + base, p.c);
-    const dt_rsrc V = dt_make_rsrc((const __bf16*)p.v + base, p.c);
+    const int d = p.d, pitch = 2 * d;                  // d <= 128, zero-padded to 128 columns
+    const int tile_pitch = TILE_ROWS * pitch;          // bytes between 64-row tiles in global memory
+    const dt_rsrc K = dt_make_rsrc((const __bf16*)p.k + base, p.c, pitch);
+    const dt_rsrc V = dt_make_rsrc((const __bf16*)p.v + base, p.c, pitch);
     float* O = p.o + base;
     float* L = p.lse + b * p.stat_stride_b + hd * p.stat_stride_h;
 
@@ -218,20 +221,20 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int r = 4 * LPW * wave + 4 * j + lr;     // tile row this lane fills with load j
-            kg[j] = r * 256 + ((pc ^ (r & 15)) << 4);
+            kg[j] = r * pitch + ((pc ^ (r & 15)) << 4);
         }
         // V's swizzle depends on the row within the 4-row group only, so its four pieces
-        // differ by exactly 1 KiB: one lane offset, the rest goes into the scalar offset
-        vg0 = (4 * LPW * wave + lr) * 256 + ((pc ^ (lr << 2)) << 4);
+        // differ by exactly four rows: one lane offset, the rest goes into the scalar offset
+        vg0 = (4 * LPW * wave + lr) * pitch + ((pc ^ (lr << 2)) << 4);
     }
 
     // first tiles on their way while the running state is loaded
     load_tile_direct(K, 0, k_lds0, kg, wave);
-    load_v_tile_direct(V, 0, v_lds0, vg0, wave);
-    load_tile_direct(K, TILE_BYTES, k_lds1, kg, wave);     // n_kt >= 2 always
+    load_v_tile_direct(V, 0, v_lds0, vg0, wave, pitch);
+    load_tile_direct(K, tile_pitch, k_lds1, kg, wave);     // n_kt >= 2 always
 
     bf16x8 qf[8];
-    load_b_frags(qf, Q + (int64_t)a * D, h);
+    load_b_frags(qf, Q + (int64_t)a * d, h, d);
     const float kappa = p.scale * LOG2E;
     float m = L[a] * LOG2E;                   // -inf stays -inf
     float l = (h == 0) ? 1.f : 0.f;           // the two half-waves hold partial row sums
@@ -240,7 +243,9 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            const float4 x = *reinterpret_cast<const float4*>(O + (int64_t)a * D + 32 * mb + 8 * g + 4 * h);
+            const int col = 32 * mb + 8 * g + 4 * h;
+            float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (col < d) x = *reinterpret_cast<const float4*>(O + (int64_t)a * d + col);
             oacc[mb][4 * g + 0] = x.x; oacc[mb][4 * g + 1] = x.y;
             oacc[mb][4 * g + 2] = x.z; oacc[mb][4 * g + 3] = x.w;
         }
@@ -282,8 +287,8 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
                                        k_cur + TILE_BYTES / 2, v_prv + TILE_BYTES / 2, mask_base - 64 * t);
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-        if (HOT || t + 2 < n_kt) load_tile_direct(K, (t + 2) * TILE_BYTES, k_cur, kg, wave);
-        if (HOT || t + 1 < n_kt) load_v_tile_direct(V, (t + 1) * TILE_BYTES, v_prv, vg0, wave);
+        if (HOT || t + 2 < n_kt) load_tile_direct(K, (t + 2) * tile_pitch, k_cur, kg, wave);
+        if (HOT || t + 1 < n_kt) load_v_tile_direct(V, (t + 1) * tile_pitch, v_prv, vg0, wave, pitch);
         step<!LAST, true, true, MASK>(s_b, s_a, p_b, p_a, oacc, qf, m, l, kappa, kaddr, vaddr, k_nxt, v_cur,
                                       mask_base - 64 * t - 32);
     };
@@ -347,7 +352,8 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
             float4 x;
             x.x = oacc[mb][4 * g + 0] * inv; x.y = oacc[mb][4 * g + 1] * inv;
             x.z = oacc[mb][4 * g + 2] * inv; x.w = oacc[mb][4 * g + 3] * inv;
-            *reinterpret_cast<float4*>(O + (int64_t)a * D + 32 * mb + 8 * g + 4 * h) = x;
+            const int col = 32 * mb + 8 * g + 4 * h;
+            if (col < d) *reinterpret_cast<float4*>(O + (int64_t)a * d + col) = x;
         }
     if (h == 0) L[a] = (m + __builtin_amdgcn_logf(l_tot)) * LN2;
 }
@@ -358,7 +364,7 @@ bool fwd_mfma_supported(const StepArgs& a, int dtype) {
     // c <= 2^22 rows: a shard matrix (256 bytes per row) stays inside a buffer descriptor's
     // 32-bit byte range with room to spare
     // ... and 16-byte aligned rows for every (batch, head)
-    return dtype == SA_BF16 && a.d == D && a.c % BM == 0 && a.c <= (1 << 22) && a.stride_b % 8 == 0 &&
+    return dtype == SA_BF16 && a.d <= D && a.d % 4 == 0 && a.c % BM == 0 && a.c <= (1 << 22) && a.stride_b % 8 == 0 &&
            a.stride_h % 8 == 0;
 }
 

@@ -19,7 +19,7 @@ namespace sa {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int TD = 128;          // tile columns = head dimension
+constexpr int TD = 128;          // tile columns: head dimensions up to 128 are zero-padded to it
 constexpr int TR = 64;           // tile rows streamed per iteration
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
@@ -54,12 +54,16 @@ typedef __attribute__((address_space(3))) s16x4 lds_s16x4_t;
 __device__ inline int dt_swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
 
 // byte offsets (within a tile, global side) of the 4 pieces this lane fetches
-__device__ inline void dt_load_offsets(uint32_t (&g)[4], int lane, int wave) {
+// (pitch = bytes between rows in global memory = 2 d; a lane fetches 16 bytes at logical chunk
+// position pc ^ f(r) of its row whatever d is: past the row's end it picks up the following
+// rows, past the matrix's end zeros, and all of that lands in the padding columns >= d that
+// the other, zero-padded operand of every product cancels)
+__device__ inline void dt_load_offsets(uint32_t (&g)[4], int lane, int wave, int pitch) {
     const int lr = lane >> 4, pc = lane & 15;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int r = 16 * wave + 4 * j + lr;
-        g[j] = r * 256 + ((pc ^ dt_swz(r)) << 4);
+        g[j] = r * pitch + ((pc ^ dt_swz(r)) << 4);
     }
 }
 // The loads go through a buffer descriptor held in scalar registers: the tile's byte
@@ -75,12 +79,12 @@ __device__ inline void dt_load_offsets(uint32_t (&g)[4], int lane, int wave) {
 // buffer is read, a barrier after its last read before it is requested again.  The
 // "memory" clobber keeps the compiler from moving LDS accesses across the request.
 typedef int dt_rsrc __attribute__((ext_vector_type(4)));
-__device__ inline dt_rsrc dt_make_rsrc(const void* matrix, int rows) {
+__device__ inline dt_rsrc dt_make_rsrc(const void* matrix, int rows, int pitch) {
     const uint64_t a = reinterpret_cast<uint64_t>(matrix);
     dt_rsrc r;
     r[0] = (int)(uint32_t)a;
     r[1] = (int)((uint32_t)(a >> 32) & 0xffffu);
-    r[2] = rows * (TD * 2);
+    r[2] = rows * pitch;          // per-dword range check: reads past the matrix return 0
     r[3] = 0x00020000;
     return r;
 }
@@ -172,10 +176,22 @@ __device__ inline void decode_block(int linear, int n_tiles, int n_bh, int& rank
     bh = grp * HEAD_GROUP + (within - rank * heads);
 }
 
-// 128-column row of `g` as B-operand fragments: 8 k-steps of 16
-__device__ inline void load_b_frags(bf16x8 (&f)[8], const __bf16* __restrict__ row, int h) {
+// Row of d <= 128 elements (d a multiple of 4) as B-operand fragments, 8 k-steps of 16,
+// zero-padded to 128 columns.  Nothing beyond the row is read.
+__device__ inline void load_b_frags(bf16x8 (&f)[8], const __bf16* __restrict__ row, int h, int d) {
+    typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) f[ks] = *reinterpret_cast<const bf16x8*>(row + 16 * ks + 8 * h);
+    for (int ks = 0; ks < 8; ++ks) {
+        const int col = 16 * ks + 8 * h;
+        if (col + 8 <= d) {
+            f[ks] = *reinterpret_cast<const bf16x8*>(row + col);
+        } else {
+            bf16x4 lo = {0, 0, 0, 0};
+            if (col + 4 <= d) lo = *reinterpret_cast<const bf16x4*>(row + col);
+            const bf16x4 z = {0, 0, 0, 0};
+            f[ks] = __builtin_shufflevector(lo, z, 0, 1, 2, 3, 4, 5, 6, 7);
+        }
+    }
 }
 
 }  // namespace sa

@@ -69,6 +69,12 @@ def test_mfma_bf16_backward(layout, B, H, S, N):
     _check(B, H, S, 128, N, layout, torch.bfloat16, seed=S + N + 5, use_driver=(N != 2))
 
 
+@pytest.mark.parametrize("layout", [sa.CONTIGUOUS, sa.STRIPED])
+@pytest.mark.parametrize("d", [100, 64, 72, 4, 124])
+def test_mfma_bf16_backward_padded_head_dimension(layout, d):
+    _check(1, 2, 768, d, 3, layout, torch.bfloat16, seed=2000 + d, use_driver=True)
+
+
 def test_mfma_backward_is_deterministic():
     B, H, S, d, N = 1, 2, 1024, 128, 2
     Q, K, V, dO = (x.cuda() for x in inputs.qkv(B, H, S, d, 32, torch.bfloat16, with_dout=True))

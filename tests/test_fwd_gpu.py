@@ -120,6 +120,15 @@ def test_mfma_bf16_ring(layout, B, H, S, N):
 
 
 @pytest.mark.parametrize("layout", [sa.CONTIGUOUS, sa.STRIPED])
+@pytest.mark.parametrize("d", [100, 64, 72, 4, 124])
+def test_mfma_bf16_padded_head_dimension(layout, d):
+    # d < 128 runs on the matrix-core kernel zero-padded to 128 columns; 100 is the head
+    # dimension of Table 1's 3B model (half a 16-byte chunk at the row end), 72 ends on a
+    # chunk, 124 leaves one group of four, 4 is the smallest
+    _check_ring(1, 2, 1024, d, 4, layout, torch.bfloat16, seed=1000 + d, use_driver=True)
+
+
+@pytest.mark.parametrize("layout", [sa.CONTIGUOUS, sa.STRIPED])
 def test_mfma_bf16_scale_and_order(layout):
     pairs = [(j, k) for j in range(4) for k in range(4)]
     np.random.default_rng(2).shuffle(pairs)
