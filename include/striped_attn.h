@@ -6,10 +6,12 @@
  * Conventions common to every entry point
  *  - All tensor pointers are DEVICE pointers unless a parameter says "host".
  *    The caller owns every buffer; the library allocates no device memory.
- *  - Q/K/V/dO/O/dQ/dK/dV are laid out [B, H, rows, d] with d contiguous and
- *    consecutive rows d elements apart; batch and head strides are given in
- *    elements.  A device's shard of c rows is a row offset into such a tensor.
- *    LSE and delta are [B, H, rows] fp32 with their own batch/head strides.
+ *  - Q/K/V/dO/O/dQ/dK/dV are indexed [batch, head, row, 0..d) with d contiguous;
+ *    batch, head and row strides are given in elements and are the same for all
+ *    of them, so both [B, H, rows, d] (stride_s = d) and [B, rows, H, d]
+ *    (stride_h = d, stride_s = H d) memory orders work.  A device's shard of c
+ *    rows is a row offset into such a tensor.  LSE and delta are [B, H, rows]
+ *    fp32 (rows contiguous) with their own batch/head strides.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    Calls only enqueue work; they do not synchronise, except sa_ring_fwd /
  *    sa_ring_bwd when asked for per-step timings.
@@ -53,6 +55,9 @@ typedef struct {
                               (d < 128 zero-padded to 128 columns) */
     int64_t stride_b;      /* elements between batches in Q/K/V/dO/O/dQ/dK/dV */
     int64_t stride_h;      /* elements between heads in the same tensors */
+    int64_t stride_s;      /* elements between consecutive rows; 0 selects d.  A multiple of 4,
+                              >= d.  Either stride_h >= c * stride_s (heads apart) or
+                              stride_s >= H * stride_h (heads interleaved within a row step) */
     int64_t stat_stride_b; /* elements between batches in LSE / delta */
     int64_t stat_stride_h; /* elements between heads in LSE / delta */
     int32_t dtype;         /* sa_dtype of Q/K/V/dO (O, LSE, delta, dQ, dK, dV are fp32) */

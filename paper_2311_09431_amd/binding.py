@@ -22,7 +22,7 @@ _lib = None
 class SaShape(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("c", ctypes.c_int32),
                 ("d", ctypes.c_int32), ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64),
-                ("stat_stride_b", ctypes.c_int64), ("stat_stride_h", ctypes.c_int64),
+                ("stride_s", ctypes.c_int64), ("stat_stride_b", ctypes.c_int64), ("stat_stride_h", ctypes.c_int64),
                 ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float)]
 
 
@@ -99,12 +99,13 @@ def _dtype_code(t):
 
 
 def shard_shape(x, c, lse=None, scale=None):
-    """sa_shape of a c-row shard of x = [B, H, rows, d] (rows contiguous, d apart)."""
+    """sa_shape of a c-row shard of x indexed [B, H, rows, d] (d contiguous; any batch, head
+    and row strides, e.g. a [B, rows, H, d] tensor viewed through permute(0, 2, 1, 3))."""
     B, H, rows, d = x.shape
-    if x.stride(3) != 1 or x.stride(2) != d:
-        raise ValueError("rows of [B, H, rows, d] must be contiguous")
+    if x.stride(3) != 1:
+        raise ValueError("the head dimension must be contiguous")
     ssb, ssh = (lse.stride(0), lse.stride(1)) if lse is not None else (H * rows, rows)
-    return SaShape(B, H, c, d, x.stride(0), x.stride(1), ssb, ssh, _dtype_code(x),
+    return SaShape(B, H, c, d, x.stride(0), x.stride(1), x.stride(2), ssb, ssh, _dtype_code(x),
                    float(scale) if scale else 0.0)
 
 

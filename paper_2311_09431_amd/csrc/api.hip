@@ -12,6 +12,8 @@ using sa::StepArgs;
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+inline int64_t row_stride(const sa_shape* s) { return s->stride_s > 0 ? s->stride_s : s->d; }
+
 int check_shape(const sa_shape* s) {
     if (!s) return SA_ERR_NULL;
     if (s->dtype != SA_F32 && s->dtype != SA_BF16) return SA_ERR_DTYPE;
@@ -19,10 +21,27 @@ int check_shape(const sa_shape* s) {
     if ((int64_t)s->B * s->H > 65535) return SA_ERR_SHAPE;
     const int dmul = 4;      // rows are read four elements at a time (16 or 8 bytes)
     if (s->d % dmul) return SA_ERR_SHAPE;
-    if (s->stride_h < (int64_t)s->c * s->d || s->stat_stride_h < s->c) return SA_ERR_SHAPE;
-    if (s->B > 1 && (s->stride_b < s->stride_h || s->stat_stride_b < s->stat_stride_h))
+    const int64_t ss = row_stride(s);
+    if (ss < s->d || s->stat_stride_h < s->c) return SA_ERR_SHAPE;
+    // heads apart ([B, H, rows, d]-like) or interleaved within a row step ([B, rows, H, d]-like)
+    const bool heads_apart = s->stride_h >= (int64_t)s->c * ss;
+    const bool heads_inside = s->stride_h >= s->d && ss >= (int64_t)s->H * s->stride_h;
+    if (!heads_apart && !heads_inside) return SA_ERR_SHAPE;
+    if (s->B > 1 && (s->stride_b < (heads_apart ? s->stride_h : (int64_t)s->c * ss) ||
+                     s->stat_stride_b < s->stat_stride_h))
         return SA_ERR_SHAPE;
-    if (s->stride_b % dmul || s->stride_h % dmul) return SA_ERR_ALIGN;
+    if (s->stride_b % dmul || s->stride_h % dmul || ss % dmul) return SA_ERR_ALIGN;
+    return SA_OK;
+}
+
+// the ring drivers address N shards of c rows inside the same tensors
+int check_ring_extent(const sa_shape* s, int N) {
+    const int64_t ss = row_stride(s), rows = (int64_t)N * s->c;
+    const bool heads_apart = s->stride_h >= rows * ss;
+    const bool heads_inside = s->stride_h >= s->d && ss >= (int64_t)s->H * s->stride_h;
+    if (!heads_apart && !heads_inside) return SA_ERR_SHAPE;
+    if (s->B > 1 && !heads_apart && s->stride_b < rows * ss) return SA_ERR_SHAPE;
+    if (s->stat_stride_h < rows) return SA_ERR_SHAPE;
     return SA_OK;
 }
 
@@ -50,6 +69,7 @@ StepArgs make_args(const sa_shape* s) {
     a.B = s->B; a.H = s->H; a.c = s->c; a.d = s->d;
     a.stride_b = s->stride_b; a.stride_h = s->stride_h;
     a.stat_stride_b = s->stat_stride_b; a.stat_stride_h = s->stat_stride_h;
+    a.stride_s = row_stride(s);
     a.scale = s->softmax_scale > 0.f ? s->softmax_scale : 1.0f / sqrtf((float)s->d);
     return a;
 }
@@ -218,12 +238,11 @@ int sa_ring_fwd_tiled(const void* Q, const void* K, const void* V, float* O, flo
     if (int e = check_skip(shape, skip_bq, skip_bk)) return e;
     if (N < 1 || q_dev_only >= N) return SA_ERR_DEV;
     if (layout != SA_CONTIGUOUS && layout != SA_STRIPED) return SA_ERR_LAYOUT;
-    if (shape->stride_h < (int64_t)N * shape->c * shape->d || shape->stat_stride_h < (int64_t)N * shape->c)
-        return SA_ERR_SHAPE;
+    if (int e = check_ring_extent(shape, N)) return e;
     if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return SA_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
     const size_t es = elt_size(shape->dtype);
-    const int64_t shard = (int64_t)shape->c * shape->d;
+    const int64_t shard = (int64_t)shape->c * row_stride(shape);     // elements between shards
     auto in_at = [&](const void* p, int dev) { return (const char*)p + (size_t)dev * shard * es; };
     if (step_ms) for (int i = 0; i < N * N; ++i) step_ms[i] = 0.f;
     const int j0 = q_dev_only >= 0 ? q_dev_only : 0, j1 = q_dev_only >= 0 ? q_dev_only + 1 : N;
@@ -258,14 +277,13 @@ int sa_ring_bwd_tiled(const void* Q, const void* K, const void* V, const void* d
     if (int e = check_skip(shape, skip_bq, skip_bk)) return e;
     if (N < 1 || q_dev_only >= N) return SA_ERR_DEV;
     if (layout != SA_CONTIGUOUS && layout != SA_STRIPED) return SA_ERR_LAYOUT;
-    if (shape->stride_h < (int64_t)N * shape->c * shape->d || shape->stat_stride_h < (int64_t)N * shape->c)
-        return SA_ERR_SHAPE;
+    if (int e = check_ring_extent(shape, N)) return e;
     if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(dO) || !aligned16(O) ||
         !aligned16(dQ) || !aligned16(dK) || !aligned16(dV))
         return SA_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
     const size_t es = elt_size(shape->dtype);
-    const int64_t shard = (int64_t)shape->c * shape->d;
+    const int64_t shard = (int64_t)shape->c * row_stride(shape);     // elements between shards
     auto in_at = [&](const void* p, int dev) { return (const char*)p + (size_t)dev * shard * es; };
     if (step_ms) for (int i = 0; i < N * N; ++i) step_ms[i] = 0.f;
     const int j0 = q_dev_only >= 0 ? q_dev_only : 0, j1 = q_dev_only >= 0 ? q_dev_only + 1 : N;

@@ -112,10 +112,12 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
     const int64_t base = b * p.stride_b + hd * p.stride_h;
     const int64_t sbase = b * p.stat_stride_b + hd * p.stat_stride_h;
     const __bf16* Q = (const __bf16*)p.q + base;
-    const int d = p.d, pitch = 2 * d;                  // d <= 128, zero-padded to 128 columns
+    const int d = p.d;                                 // d <= 128, zero-padded to 128 columns
+    const int64_t ss = p.stride_s;                     // elements between consecutive rows
+    const int pitch = 2 * (int)ss;                     // bytes
     const int tile_pitch = DT_ROWS * pitch;            // bytes between 64-row tiles in global memory
-    const dt_rsrc Kr = dt_make_rsrc((const __bf16*)p.k + base, p.c, pitch);
-    const dt_rsrc Vr = dt_make_rsrc((const __bf16*)p.v + base, p.c, pitch);
+    const dt_rsrc Kr = dt_make_rsrc((const __bf16*)p.k + base, p.c, pitch, d);
+    const dt_rsrc Vr = dt_make_rsrc((const __bf16*)p.v + base, p.c, pitch, d);
     const __bf16* G = (const __bf16*)p.dout + base;
     float* DQ = p.dq + base;
 
@@ -140,8 +142,8 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
     dt_load(Vr, tile_pitch, v_lds1, gl, wave);
 
     bf16x8 qf[8], gf[8];
-    load_b_frags(qf, Q + (int64_t)a * d, h, d);
-    load_b_frags(gf, G + (int64_t)a * d, h, d);
+    load_b_frags(qf, Q + (int64_t)a * ss, h, d);
+    load_b_frags(gf, G + (int64_t)a * ss, h, d);
     const float kappa = p.scale * LOG2E;
     float lse2 = p.lse[sbase + a] * LOG2E;
     float delta = p.delta[sbase + a];
@@ -230,7 +232,7 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
         for (int g = 0; g < 4; ++g) {
             const int col = 32 * mb + 8 * g + 4 * h;
             if (col >= d) continue;                       // padding columns
-            float4* dst = reinterpret_cast<float4*>(DQ + (int64_t)a * d + col);
+            float4* dst = reinterpret_cast<float4*>(DQ + (int64_t)a * ss + col);
             float4 x = *dst;
             x.x = fmaf(p.scale, acc[mb][4 * g + 0], x.x); x.y = fmaf(p.scale, acc[mb][4 * g + 1], x.y);
             x.z = fmaf(p.scale, acc[mb][4 * g + 2], x.z); x.w = fmaf(p.scale, acc[mb][4 * g + 3], x.w);
@@ -346,10 +348,12 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
     const int b = bh / p.H, hd = bh - b * p.H;
     const int64_t base = b * p.stride_b + hd * p.stride_h;
     const int64_t sbase = b * p.stat_stride_b + hd * p.stat_stride_h;
-    const int d = p.d, pitch = 2 * d;                  // d <= 128, zero-padded to 128 columns
+    const int d = p.d;                                 // d <= 128, zero-padded to 128 columns
+    const int64_t ss = p.stride_s;                     // elements between consecutive rows
+    const int pitch = 2 * (int)ss;                     // bytes
     const int tile_pitch = DT_ROWS * pitch;            // bytes between 64-row tiles in global memory
-    const dt_rsrc Qr = dt_make_rsrc((const __bf16*)p.q + base, p.c, pitch);
-    const dt_rsrc Gr = dt_make_rsrc((const __bf16*)p.dout + base, p.c, pitch);
+    const dt_rsrc Qr = dt_make_rsrc((const __bf16*)p.q + base, p.c, pitch, d);
+    const dt_rsrc Gr = dt_make_rsrc((const __bf16*)p.dout + base, p.c, pitch, d);
     const __bf16* K = (const __bf16*)p.k + base;
     const __bf16* V = (const __bf16*)p.v + base;
     const float* LSE = p.lse + sbase;
@@ -397,8 +401,8 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
     stat_store(t_first + 1, stat_fetch());
 
     bf16x8 kf[8], vf[8];
-    load_b_frags(kf, K + (int64_t)key * d, h, d);
-    load_b_frags(vf, V + (int64_t)key * d, h, d);
+    load_b_frags(kf, K + (int64_t)key * ss, h, d);
+    load_b_frags(vf, V + (int64_t)key * ss, h, d);
     const float kappa = p.scale * LOG2E;
     f32x16 acck[4], accv[4];
 #pragma unroll
@@ -486,7 +490,7 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
         for (int g = 0; g < 4; ++g) {
             const int col = 32 * mb + 8 * g + 4 * h;
             if (col >= d) continue;                       // padding columns
-            const int64_t o = (int64_t)key * d + col;
+            const int64_t o = (int64_t)key * ss + col;
             float4 x = *reinterpret_cast<float4*>(DV + o);
             x.x += accv[mb][4 * g + 0]; x.y += accv[mb][4 * g + 1];
             x.z += accv[mb][4 * g + 2]; x.w += accv[mb][4 * g + 3];
@@ -501,11 +505,10 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
 }  // namespace
 
 bool bwd_mfma_supported(const StepArgs& a, int dtype) {
-    // c <= 2^22 rows: a shard matrix (256 bytes per row) stays inside a buffer descriptor's
-    // 32-bit byte range with room to spare
-    // ... and 16-byte aligned rows for every (batch, head)
-    return dtype == SA_BF16 && a.d <= D && a.d % 4 == 0 && a.c % BM == 0 && a.c <= (1 << 22) && a.stride_b % 8 == 0 &&
-           a.stride_h % 8 == 0;
+    // the tile loads address a shard through a buffer descriptor with 32-bit byte offsets:
+    // its last row must end below 2^31 bytes from its first
+    return dtype == SA_BF16 && a.d <= D && a.d % 4 == 0 && a.c % BM == 0 &&
+           (int64_t)(a.c - 1) * 2 * a.stride_s + 2 * a.d < (int64_t(1) << 31);
 }
 
 hipError_t launch_bwd_mfma(const StepArgs& a, hipStream_t st) {

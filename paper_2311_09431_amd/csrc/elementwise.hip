@@ -8,15 +8,19 @@
 
 namespace sa {
 
-// grid: (row blocks, B*H); each thread handles 4 floats of a row.
+// grid: (row blocks, B*H); each thread handles 4 floats of a row; rows are ss elements apart.
 __global__ void __launch_bounds__(256)
 state_init_kernel(float* __restrict__ o, float* __restrict__ lse, int H, int c, int d,
-                  int64_t sb, int64_t sh, int64_t ssb, int64_t ssh, float lse_value, bool touch_lse) {
+                  int64_t sb, int64_t sh, int64_t ss, int64_t ssb, int64_t ssh, float lse_value,
+                  bool touch_lse) {
     const int bh = blockIdx.y, b = bh / H, h = bh - b * H;
     float* ob = o + b * sb + h * sh;
-    const int64_t n4 = (int64_t)c * d / 4;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256)
-        reinterpret_cast<float4*>(ob)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    const int d4 = d / 4;
+    const int64_t n4 = (int64_t)c * d4;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256) {
+        const int64_t row = i / d4;
+        *reinterpret_cast<float4*>(ob + row * ss + (i - row * d4) * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
     if (touch_lse) {
         float* lb = lse + b * ssb + h * ssh;
         for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < c; i += (int64_t)gridDim.x * 256)
@@ -31,17 +35,19 @@ static unsigned row_blocks(int64_t work_items) {
     return (unsigned)g;
 }
 
+static int64_t row_stride(const sa_shape& s) { return s.stride_s > 0 ? s.stride_s : s.d; }
+
 hipError_t launch_state_init(float* o, float* lse, const sa_shape& s, hipStream_t st) {
     dim3 grid(row_blocks((int64_t)s.c * s.d / 4), s.B * s.H);
     hipLaunchKernelGGL(state_init_kernel, grid, dim3(256), 0, st, o, lse, s.H, s.c, s.d, s.stride_b,
-                       s.stride_h, s.stat_stride_b, s.stat_stride_h, -INFINITY, true);
+                       s.stride_h, row_stride(s), s.stat_stride_b, s.stat_stride_h, -INFINITY, true);
     return hipGetLastError();
 }
 
 hipError_t launch_zero_f32(float* p, const sa_shape& s, hipStream_t st) {
     dim3 grid(row_blocks((int64_t)s.c * s.d / 4), s.B * s.H);
     hipLaunchKernelGGL(state_init_kernel, grid, dim3(256), 0, st, p, (float*)nullptr, s.H, s.c, s.d,
-                       s.stride_b, s.stride_h, (int64_t)0, (int64_t)0, 0.f, false);
+                       s.stride_b, s.stride_h, row_stride(s), (int64_t)0, (int64_t)0, 0.f, false);
     return hipGetLastError();
 }
 
@@ -59,23 +65,26 @@ __device__ inline void store4<__hip_bfloat16>(__hip_bfloat16* p, float4 v) {
 template <typename OutT>
 __global__ void __launch_bounds__(256)
 finalize_kernel(const float* __restrict__ o, OutT* __restrict__ out, int H, int c, int d, int64_t sb,
-                int64_t sh) {
+                int64_t sh, int64_t ss) {
     const int bh = blockIdx.y, b = bh / H, h = bh - b * H;
     const float* ob = o + b * sb + h * sh;
     OutT* yb = out + b * sb + h * sh;
-    const int64_t n4 = (int64_t)c * d / 4;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256)
-        store4<OutT>(yb + i * 4, reinterpret_cast<const float4*>(ob)[i]);
+    const int d4 = d / 4;
+    const int64_t n4 = (int64_t)c * d4;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256) {
+        const int64_t row = i / d4, at = row * ss + (i - row * d4) * 4;
+        store4<OutT>(yb + at, *reinterpret_cast<const float4*>(ob + at));
+    }
 }
 
 hipError_t launch_finalize(const float* o, void* out, const sa_shape& s, hipStream_t st) {
     dim3 grid(row_blocks((int64_t)s.c * s.d / 4), s.B * s.H);
     if (s.dtype == SA_F32)
         hipLaunchKernelGGL(finalize_kernel<float>, grid, dim3(256), 0, st, o, (float*)out, s.H, s.c,
-                           s.d, s.stride_b, s.stride_h);
+                           s.d, s.stride_b, s.stride_h, row_stride(s));
     else
         hipLaunchKernelGGL(finalize_kernel<__hip_bfloat16>, grid, dim3(256), 0, st, o,
-                           (__hip_bfloat16*)out, s.H, s.c, s.d, s.stride_b, s.stride_h);
+                           (__hip_bfloat16*)out, s.H, s.c, s.d, s.stride_b, s.stride_h, row_stride(s));
     return hipGetLastError();
 }
 
@@ -99,12 +108,12 @@ __device__ inline float4 load4<__hip_bfloat16>(const __hip_bfloat16* p) {
 template <typename T>
 __global__ void __launch_bounds__(256)
 bwd_preprocess_kernel(const float* __restrict__ o, const T* __restrict__ dout, float* __restrict__ delta,
-                      int H, int c, int d, int64_t sb, int64_t sh, int64_t ssb, int64_t ssh) {
+                      int H, int c, int d, int64_t sb, int64_t sh, int64_t ss, int64_t ssb, int64_t ssh) {
     const int bh = blockIdx.y, b = bh / H, h = bh - b * H;
     const int g = threadIdx.x >> 4, l = threadIdx.x & 15;
     for (int64_t row = (int64_t)blockIdx.x * 16 + g; row < c; row += (int64_t)gridDim.x * 16) {
-        const float* orow = o + b * sb + h * sh + row * d;
-        const T* grow = dout + b * sb + h * sh + row * d;
+        const float* orow = o + b * sb + h * sh + row * ss;
+        const T* grow = dout + b * sb + h * sh + row * ss;
         float acc = 0.f;
         for (int t = l * 4; t < d; t += 64) {
             float4 x = *reinterpret_cast<const float4*>(orow + t);
@@ -126,12 +135,12 @@ hipError_t launch_bwd_preprocess(const float* o, const void* dout, float* delta,
     dim3 grid((unsigned)g, s.B * s.H);
     if (s.dtype == SA_F32)
         hipLaunchKernelGGL(bwd_preprocess_kernel<float>, grid, dim3(256), 0, st, o, (const float*)dout,
-                           delta, s.H, s.c, s.d, s.stride_b, s.stride_h, s.stat_stride_b,
+                           delta, s.H, s.c, s.d, s.stride_b, s.stride_h, row_stride(s), s.stat_stride_b,
                            s.stat_stride_h);
     else
         hipLaunchKernelGGL(bwd_preprocess_kernel<__hip_bfloat16>, grid, dim3(256), 0, st, o,
                            (const __hip_bfloat16*)dout, delta, s.H, s.c, s.d, s.stride_b, s.stride_h,
-                           s.stat_stride_b, s.stat_stride_h);
+                           row_stride(s), s.stat_stride_b, s.stat_stride_h);
     return hipGetLastError();
 }
 

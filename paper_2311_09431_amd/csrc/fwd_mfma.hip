@@ -180,10 +180,12 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     const int b = bh / p.H, hd = bh - b * p.H;
     const int64_t base = b * p.stride_b + hd * p.stride_h;
     const __bf16* Q = (const __bf16*)p.q + base;
-    const int d = p.d, pitch = 2 * d;                  // d <= 128, zero-padded to 128 columns
+    const int d = p.d;                                 // d <= 128, zero-padded to 128 columns
+    const int64_t ss = p.stride_s;                     // elements between consecutive rows
+    const int pitch = 2 * (int)ss;                     // bytes
     const int tile_pitch = TILE_ROWS * pitch;          // bytes between 64-row tiles in global memory
-    const dt_rsrc K = dt_make_rsrc((const __bf16*)p.k + base, p.c, pitch);
-    const dt_rsrc V = dt_make_rsrc((const __bf16*)p.v + base, p.c, pitch);
+    const dt_rsrc K = dt_make_rsrc((const __bf16*)p.k + base, p.c, pitch, d);
+    const dt_rsrc V = dt_make_rsrc((const __bf16*)p.v + base, p.c, pitch, d);
     float* O = p.o + base;
     float* L = p.lse + b * p.stat_stride_b + hd * p.stat_stride_h;
 
@@ -234,7 +236,7 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     load_tile_direct(K, tile_pitch, k_lds1, kg, wave);     // n_kt >= 2 always
 
     bf16x8 qf[8];
-    load_b_frags(qf, Q + (int64_t)a * d, h, d);
+    load_b_frags(qf, Q + (int64_t)a * ss, h, d);
     const float kappa = p.scale * LOG2E;
     float m = L[a] * LOG2E;                   // -inf stays -inf
     float l = (h == 0) ? 1.f : 0.f;           // the two half-waves hold partial row sums
@@ -245,7 +247,7 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
         for (int g = 0; g < 4; ++g) {
             const int col = 32 * mb + 8 * g + 4 * h;
             float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (col < d) x = *reinterpret_cast<const float4*>(O + (int64_t)a * d + col);
+            if (col < d) x = *reinterpret_cast<const float4*>(O + (int64_t)a * ss + col);
             oacc[mb][4 * g + 0] = x.x; oacc[mb][4 * g + 1] = x.y;
             oacc[mb][4 * g + 2] = x.z; oacc[mb][4 * g + 3] = x.w;
         }
@@ -353,7 +355,7 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
             x.x = oacc[mb][4 * g + 0] * inv; x.y = oacc[mb][4 * g + 1] * inv;
             x.z = oacc[mb][4 * g + 2] * inv; x.w = oacc[mb][4 * g + 3] * inv;
             const int col = 32 * mb + 8 * g + 4 * h;
-            if (col < d) *reinterpret_cast<float4*>(O + (int64_t)a * d + col) = x;
+            if (col < d) *reinterpret_cast<float4*>(O + (int64_t)a * ss + col) = x;
         }
     if (h == 0) L[a] = (m + __builtin_amdgcn_logf(l_tot)) * LN2;
 }
@@ -361,11 +363,10 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
 }  // namespace
 
 bool fwd_mfma_supported(const StepArgs& a, int dtype) {
-    // c <= 2^22 rows: a shard matrix (256 bytes per row) stays inside a buffer descriptor's
-    // 32-bit byte range with room to spare
-    // ... and 16-byte aligned rows for every (batch, head)
-    return dtype == SA_BF16 && a.d <= D && a.d % 4 == 0 && a.c % BM == 0 && a.c <= (1 << 22) && a.stride_b % 8 == 0 &&
-           a.stride_h % 8 == 0;
+    // the tile loads address a shard through a buffer descriptor with 32-bit byte offsets:
+    // its last row must end below 2^31 bytes from its first
+    return dtype == SA_BF16 && a.d <= D && a.d % 4 == 0 && a.c % BM == 0 &&
+           (int64_t)(a.c - 1) * 2 * a.stride_s + 2 * a.d < (int64_t(1) << 31);
 }
 
 hipError_t launch_fwd_mfma(const StepArgs& a, hipStream_t st) {

@@ -69,13 +69,14 @@ fwd_generic_kernel(StepArgs p) {
     float* O = p.o + base;
     float* L = p.lse + b * p.stat_stride_b + h * p.stat_stride_h;
     const int d = p.d;
+    const int64_t ss = p.stride_s;        // elements between consecutive rows
 
     for (int r = 0; r < kRowsPerWave; ++r) {
         const int a = (blockIdx.x * kWaves + wave) * kRowsPerWave + r;
         if (a >= p.c) break;                                  // wave-uniform
         const int nkeys = keys_for_query(a, p.c, p.kind, p.off);
         if (nkeys == 0) continue;                             // row sees nothing: state unchanged
-        for (int t = lane; t < d; t += 64) q_lds[wave][t] = ld<T>(Q + (int64_t)a * d + t);
+        for (int t = lane; t < d; t += 64) q_lds[wave][t] = ld<T>(Q + (int64_t)a * ss + t);
         // running state: weight exp(lse) with l = 1 (or nothing yet)
         float m = L[a];
         float l = (m == -INFINITY) ? 0.f : 1.f;
@@ -83,13 +84,13 @@ fwd_generic_kernel(StepArgs p) {
 #pragma unroll
         for (int i = 0; i < kMaxD / 64; ++i) {
             const int t = lane + 64 * i;
-            acc[i] = (t < d) ? O[(int64_t)a * d + t] : 0.f;
+            acc[i] = (t < d) ? O[(int64_t)a * ss + t] : 0.f;
         }
         __builtin_amdgcn_wave_barrier();
         for (int b0 = 0; b0 < nkeys; b0 += 64) {
             const int key = b0 + lane;
             const bool valid = key < nkeys;
-            float s = valid ? p.scale * dot_row<T>(q_lds[wave], K + (int64_t)key * d, d) : -INFINITY;
+            float s = valid ? p.scale * dot_row<T>(q_lds[wave], K + (int64_t)key * ss, d) : -INFINITY;
             const float m_new = fmaxf(m, wave_max(s));        // finite: lane 0 is always valid
             const float alpha = (m == -INFINITY) ? 0.f : expf(m - m_new);
             const float pr = valid ? expf(s - m_new) : 0.f;
@@ -99,7 +100,7 @@ fwd_generic_kernel(StepArgs p) {
             const int nk = min(64, nkeys - b0);
             for (int kk = 0; kk < nk; ++kk) {
                 const float pk = __shfl(pr, kk);
-                const T* vrow = V + (int64_t)(b0 + kk) * d;
+                const T* vrow = V + (int64_t)(b0 + kk) * ss;
 #pragma unroll
                 for (int i = 0; i < kMaxD / 64; ++i) {
                     const int t = lane + 64 * i;
@@ -112,7 +113,7 @@ fwd_generic_kernel(StepArgs p) {
 #pragma unroll
         for (int i = 0; i < kMaxD / 64; ++i) {
             const int t = lane + 64 * i;
-            if (t < d) O[(int64_t)a * d + t] = acc[i] * inv;
+            if (t < d) O[(int64_t)a * ss + t] = acc[i] * inv;
         }
         if (lane == 0) L[a] = m + logf(l);
         __builtin_amdgcn_wave_barrier();
@@ -136,6 +137,7 @@ bwd_dq_generic_kernel(StepArgs p) {
     const float* L = p.lse + b * p.stat_stride_b + h * p.stat_stride_h;
     const float* D = p.delta + b * p.stat_stride_b + h * p.stat_stride_h;
     const int d = p.d;
+    const int64_t ss = p.stride_s;        // elements between consecutive rows
 
     for (int r = 0; r < kRowsPerWave; ++r) {
         const int a = (blockIdx.x * kWaves + wave) * kRowsPerWave + r;
@@ -143,8 +145,8 @@ bwd_dq_generic_kernel(StepArgs p) {
         const int nkeys = keys_for_query(a, p.c, p.kind, p.off);
         if (nkeys == 0) continue;
         for (int t = lane; t < d; t += 64) {
-            q_lds[wave][t] = ld<T>(Q + (int64_t)a * d + t);
-            g_lds[wave][t] = ld<T>(G + (int64_t)a * d + t);
+            q_lds[wave][t] = ld<T>(Q + (int64_t)a * ss + t);
+            g_lds[wave][t] = ld<T>(G + (int64_t)a * ss + t);
         }
         const float lse = L[a], delta = D[a];
         float acc[kMaxD / 64];
@@ -155,15 +157,15 @@ bwd_dq_generic_kernel(StepArgs p) {
             const int key = b0 + lane;
             float ds = 0.f;
             if (key < nkeys) {
-                const float s = p.scale * dot_row<T>(q_lds[wave], K + (int64_t)key * d, d);
+                const float s = p.scale * dot_row<T>(q_lds[wave], K + (int64_t)key * ss, d);
                 const float pr = expf(s - lse);
-                const float dp = dot_row<T>(g_lds[wave], V + (int64_t)key * d, d);
+                const float dp = dot_row<T>(g_lds[wave], V + (int64_t)key * ss, d);
                 ds = pr * (dp - delta);
             }
             const int nk = min(64, nkeys - b0);
             for (int kk = 0; kk < nk; ++kk) {
                 const float x = __shfl(ds, kk);
-                const T* krow = K + (int64_t)(b0 + kk) * d;
+                const T* krow = K + (int64_t)(b0 + kk) * ss;
 #pragma unroll
                 for (int i = 0; i < kMaxD / 64; ++i) {
                     const int t = lane + 64 * i;
@@ -174,7 +176,7 @@ bwd_dq_generic_kernel(StepArgs p) {
 #pragma unroll
         for (int i = 0; i < kMaxD / 64; ++i) {
             const int t = lane + 64 * i;
-            if (t < d) DQ[(int64_t)a * d + t] += p.scale * acc[i];
+            if (t < d) DQ[(int64_t)a * ss + t] += p.scale * acc[i];
         }
         __builtin_amdgcn_wave_barrier();
     }
@@ -198,6 +200,7 @@ bwd_dkv_generic_kernel(StepArgs p) {
     const float* L = p.lse + b * p.stat_stride_b + h * p.stat_stride_h;
     const float* D = p.delta + b * p.stat_stride_b + h * p.stat_stride_h;
     const int d = p.d;
+    const int64_t ss = p.stride_s;        // elements between consecutive rows
 
     for (int r = 0; r < kRowsPerWave; ++r) {
         const int key = (blockIdx.x * kWaves + wave) * kRowsPerWave + r;
@@ -206,8 +209,8 @@ bwd_dkv_generic_kernel(StepArgs p) {
         const int a_first = (p.kind == MASK_FULL) ? 0 : key + p.off;
         if (a_first >= p.c) continue;
         for (int t = lane; t < d; t += 64) {
-            k_lds[wave][t] = ld<T>(K + (int64_t)key * d + t);
-            v_lds[wave][t] = ld<T>(V + (int64_t)key * d + t);
+            k_lds[wave][t] = ld<T>(K + (int64_t)key * ss + t);
+            v_lds[wave][t] = ld<T>(V + (int64_t)key * ss + t);
         }
         float acc_k[kMaxD / 64], acc_v[kMaxD / 64];
 #pragma unroll
@@ -217,16 +220,16 @@ bwd_dkv_generic_kernel(StepArgs p) {
             const int a = a0 + lane;
             float pr = 0.f, ds = 0.f;
             if (a < p.c) {
-                const float s = p.scale * dot_row<T>(k_lds[wave], Q + (int64_t)a * d, d);
+                const float s = p.scale * dot_row<T>(k_lds[wave], Q + (int64_t)a * ss, d);
                 pr = expf(s - L[a]);
-                const float dp = dot_row<T>(v_lds[wave], G + (int64_t)a * d, d);
+                const float dp = dot_row<T>(v_lds[wave], G + (int64_t)a * ss, d);
                 ds = pr * (dp - D[a]);
             }
             const int na = min(64, p.c - a0);
             for (int kk = 0; kk < na; ++kk) {
                 const float x = __shfl(pr, kk), y = __shfl(ds, kk);
-                const T* grow = G + (int64_t)(a0 + kk) * d;
-                const T* qrow = Q + (int64_t)(a0 + kk) * d;
+                const T* grow = G + (int64_t)(a0 + kk) * ss;
+                const T* qrow = Q + (int64_t)(a0 + kk) * ss;
 #pragma unroll
                 for (int i = 0; i < kMaxD / 64; ++i) {
                     const int t = lane + 64 * i;
@@ -241,8 +244,8 @@ bwd_dkv_generic_kernel(StepArgs p) {
         for (int i = 0; i < kMaxD / 64; ++i) {
             const int t = lane + 64 * i;
             if (t < d) {
-                DV[(int64_t)key * d + t] += acc_v[i];
-                DK[(int64_t)key * d + t] += p.scale * acc_k[i];
+                DV[(int64_t)key * ss + t] += acc_v[i];
+                DK[(int64_t)key * ss + t] += p.scale * acc_k[i];
             }
         }
         __builtin_amdgcn_wave_barrier();

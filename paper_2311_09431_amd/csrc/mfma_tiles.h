@@ -54,7 +54,7 @@ typedef __attribute__((address_space(3))) s16x4 lds_s16x4_t;
 __device__ inline int dt_swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
 
 // byte offsets (within a tile, global side) of the 4 pieces this lane fetches
-// (pitch = bytes between rows in global memory = 2 d; a lane fetches 16 bytes at logical chunk
+// (pitch = bytes between rows in global memory, >= 2 d; a lane fetches 16 bytes at logical chunk
 // position pc ^ f(r) of its row whatever d is: past the row's end it picks up the following
 // rows, past the matrix's end zeros, and all of that lands in the padding columns >= d that
 // the other, zero-padded operand of every product cancels)
@@ -79,12 +79,13 @@ __device__ inline void dt_load_offsets(uint32_t (&g)[4], int lane, int wave, int
 // buffer is read, a barrier after its last read before it is requested again.  The
 // "memory" clobber keeps the compiler from moving LDS accesses across the request.
 typedef int dt_rsrc __attribute__((ext_vector_type(4)));
-__device__ inline dt_rsrc dt_make_rsrc(const void* matrix, int rows, int pitch) {
+__device__ inline dt_rsrc dt_make_rsrc(const void* matrix, int rows, int pitch, int d) {
     const uint64_t a = reinterpret_cast<uint64_t>(matrix);
     dt_rsrc r;
     r[0] = (int)(uint32_t)a;
     r[1] = (int)((uint32_t)(a >> 32) & 0xffffu);
-    r[2] = rows * pitch;          // per-dword range check: reads past the matrix return 0
+    r[2] = (rows - 1) * pitch + 2 * d;     // ends with the last row; the range check is per dword
+                                           // and reads past the end return 0
     r[3] = 0x00020000;
     return r;
 }

@@ -25,6 +25,7 @@ struct StepArgs {
     float* dv;
     int B, H, c, d;
     int64_t stride_b, stride_h, stat_stride_b, stat_stride_h;
+    int64_t stride_s;     // elements between consecutive rows (>= d)
     float scale;
     int kind;             // MaskKind (never MASK_EMPTY at launch)
     int off;              // 0 or 1 when kind == MASK_TRI

@@ -44,7 +44,7 @@ def test_step_mask_and_pairs_match_the_oracle(N, c):
 
 
 def _shape(**kw):
-    base = dict(B=1, H=2, c=64, d=64, stride_b=2 * 256 * 64, stride_h=256 * 64, stat_stride_b=512,
+    base = dict(B=1, H=2, c=64, d=64, stride_b=2 * 256 * 64, stride_h=256 * 64, stride_s=0, stat_stride_b=512,
                 stat_stride_h=256, dtype=sa.F32, softmax_scale=0.0)
     base.update(kw)
     return sa.SaShape(**base)
