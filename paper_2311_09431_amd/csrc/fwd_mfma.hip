@@ -1,7 +1,8 @@
 // Forward ring step on the CDNA4 matrix cores (bf16 operands, fp32 accumulate),
-// head dimension 128: AccumulateAttentionFragment of Algorithm 1 with the fused
-// log-sum-exp merge, skipping every 32-key sub-tile that GetMask(j, k) masks
-// entirely for a 32-query wavefront (Sec. 2.2.1).
+// head dimension up to 128 (zero-padded to 128 columns): AccumulateAttentionFragment
+// of Algorithm 1 with the fused log-sum-exp merge, skipping every 32-key sub-tile
+// that GetMask(j, k) masks entirely for a 32-query wavefront (Sec. 2.2.1); a coarser
+// skipping granularity (Sec. 3.1) can be emulated on request.
 //
 // Work decomposition.  A workgroup of 4 wavefronts owns 128 query rows; each
 // wavefront owns 32 of them for the whole kernel.  Key/value tiles of 64 rows
@@ -55,7 +56,7 @@ namespace {
 
 constexpr int NW = 4;                   // wavefronts per workgroup (8 measured the same at 32768-token shards)
 constexpr int BM = 32 * NW;             // query rows per workgroup
-constexpr int D = TD;                   // head dimension
+constexpr int D = TD;                   // columns of a tile: head dimensions below it are zero-padded
 constexpr int TILE_ROWS = 64;           // key rows per LDS tile
 constexpr int TILE_BYTES = TILE_ROWS * D * 2;   // 16 KiB
 constexpr float RESCALE_LOG2 = 8.f;
