@@ -116,6 +116,34 @@ class Runner:
         return t_f, t_b
 
 
+def cold_forward(run, layout, reps=2):
+    """Forward ring with L2 and the memory-side cache flushed before every step (a 1 GiB
+    read-modify-write), timed step by step from the host side of the C ABI: in a real ring a
+    visiting K/V shard arrives from the neighbour, not from this device's caches.  Returns the
+    [N][N] table of step durations (ms), averaged over reps."""
+    w, c, N = run.w, run.c, run.w["N"]
+    ins = run.perm if layout == sa.STRIPED else run.orig
+    flush = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda")
+    devs = range(N) if w["q_dev"] < 0 else [w["q_dev"]]
+    table = [[0.0] * N for _ in range(N)]
+    rows = lambda t, dev: t[:, :, dev * c:]
+    for _ in range(reps):
+        for j in devs:
+            sa.sa_state_init(rows(run.O, j), rows(run.LSE, j), run.shape)
+        for i in range(N):
+            for j in devs:
+                k = (j - i) % N
+                flush.add_(1)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                sa.sa_attn_step_fwd(rows(ins[0], j), rows(ins[1], k), rows(ins[2], k), rows(run.O, j),
+                                    rows(run.LSE, j), j, k, N, layout, run.shape)
+                e1.record()
+                e1.synchronize()
+                table[i][j] += e0.elapsed_time(e1) / reps
+    return table
+
+
 def summarize_steps(w, layout, table, per_pair):
     """Per-step latency / TFLOP/s rows and the worst-device latency of every round."""
     N = w["N"]
@@ -172,6 +200,8 @@ def main():
     ap.add_argument("--bwd", type=int, default=1, help="0: forward ring only (default: forward + backward)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=3)
+    ap.add_argument("--cold", action="store_true",
+                    help="also time the forward steps with the caches flushed before each one")
     ap.add_argument("--skip-granularity", default="", metavar="BQxBK",
                     help="emulate tile skipping per BQ x BK tile (Sec. 3.1 of the paper), e.g. 2048x4096; "
                          "default: the kernels' own 32 x 32")
@@ -278,6 +308,19 @@ def main():
                 tms.tiled_attention_limit(N, c, *skip, devices=None if w["q_dev"] < 0 else [w["q_dev"]]), 3),
             "worst_device_ratio_element_granularity": round(tms.attention_only_limit(N, c), 3),
         }
+    if args.cold:
+        cold = {}
+        for name, layout in (("striped", sa.STRIPED), ("contiguous", sa.CONTIGUOUS)):
+            if layout == sa.STRIPED:
+                run.one_pass(sa.STRIPED, False)          # leaves the permuted inputs in place
+            rows_c, worst_c = summarize_steps(w, layout, cold_forward(run, layout), 4)
+            live = [r for r in rows_c if r["ms"] > 0]
+            cold[name] = {"worst_device_ms_per_round": worst_c, "ring_sum_ms": round(sum(worst_c), 4),
+                          "mean_step_ms": round(sum(r["ms"] for r in live) / max(1, len(live)), 4)}
+        cold["worst_device_latency_ratio_contiguous_over_striped"] = round(
+            cold["contiguous"]["ring_sum_ms"] / max(1e-9, cold["striped"]["ring_sum_ms"]), 3)
+        cold["note"] = "forward steps, L2 and memory-side cache flushed before each step"
+        result["cold_cache"] = cold
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline()
     print(json.dumps(result))
