@@ -1,0 +1,59 @@
+"""A seeded sweep over shapes the hand-picked cases may miss: random batch, heads, block size,
+device count, head dimension, storage type, softmax scale and layout, forward and backward,
+each against the fp64 oracle with the usual tolerances.  Half of the bf16 cases are built to
+take the matrix-core kernels (c a multiple of 128, d <= 128), the rest the generic ones."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2311_09431_amd import binding as sa
+from paper_2311_09431_amd import inputs
+from tests import helpers as hp
+
+pytestmark = pytest.mark.gpu
+
+
+def _cases(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        N = int(rng.choice([1, 2, 3, 4, 5, 8]))
+        mfma = bool(i % 2)
+        if mfma:
+            c = 128 * int(rng.integers(1, 5))
+            d = int(rng.choice([128, 128, 100, 64, 96, 32]))
+            dtype = torch.bfloat16
+        else:
+            c = int(rng.integers(1, 90))
+            d = 4 * int(rng.integers(1, 41))
+            dtype = torch.float32 if rng.random() < 0.6 else torch.bfloat16
+        B, H = int(rng.integers(1, 3)), int(rng.integers(1, 4))
+        layout = sa.STRIPED if rng.random() < 0.6 else sa.CONTIGUOUS
+        scale = None if rng.random() < 0.5 else float(rng.uniform(0.02, 0.3))
+        out.append((B, H, c, N, d, dtype, layout, scale, int(rng.integers(1, 10 ** 6))))
+    return out
+
+
+@pytest.mark.parametrize("case", _cases(24, 2311_09431), ids=lambda c: "B%dH%dc%dN%dd%d" % c[:5])
+def test_random_shapes_forward_and_backward(case):
+    B, H, c, N, d, dtype, layout, scale, seed = case
+    S = c * N
+    Q, K, V, dO = inputs.qkv(B, H, S, d, seed, dtype, with_dout=True)
+    sc = scale if scale else 1.0 / np.sqrt(d)
+    Qg, Kg, Vg, Gg = (x.cuda() for x in (Q, K, V, dO))
+    Qp, Kp, Vp, Gp = (hp.to_device_order(x, N, layout) for x in (Qg, Kg, Vg, Gg))
+    O = torch.empty(B, H, S, d, dtype=torch.float32, device="cuda")
+    LSE = torch.empty(B, H, S, dtype=torch.float32, device="cuda")
+    delta = torch.empty_like(LSE)
+    grads = [torch.empty_like(O) for _ in range(3)]
+    shape = sa.shard_shape(Qp, c, LSE, scale)
+    sa.sa_ring_fwd(Qp, Kp, Vp, O, LSE, N, layout, shape)
+    sa.sa_ring_bwd(Qp, Kp, Vp, Gp, O, LSE, delta, *grads, N, layout, shape)
+    torch.cuda.synchronize()
+    back = lambda t: hp.from_device_order_host(t.cpu().numpy(), N, layout)
+    bf16 = dtype == torch.bfloat16
+    Ow, Lw = hp.oracle_forward(Q, K, V, sc)
+    assert hp.max_abs_err(back(O), Ow) <= (2e-2 if bf16 else 1e-5)
+    assert hp.max_abs_err(back(LSE), Lw) <= (1e-3 if bf16 else 1e-5)
+    for g, w in zip(grads, hp.oracle_backward(Q, K, V, dO, sc)):
+        assert hp.max_abs_err(back(g), w) <= (2e-2 if bf16 else 2e-5) * max(1.0, float(np.max(np.abs(w))))
