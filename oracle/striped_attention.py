@@ -162,6 +162,27 @@ def unstripe_permute(x, N, axis):
     return np.take(x, inv, axis=axis)
 
 
+def rope(x, pos, base=10000.0, inverse=False):
+    """Rotary position embedding of the rows of x[..., rows, d] at positions pos[rows] (or
+    pos[..., rows] broadcastable to x's leading axes): pairs (x_i, x_{i+d/2}) are rotated by
+    the angle pos * base**(-2i/d), i < d/2.  Sec. 2.3 only requires that each token keeps the
+    position id of its ORIGINAL place when the sequence is permuted; the rotation itself is
+    the usual one (rotate-half form).  inverse=True rotates by the negative angle (the
+    transpose, which maps gradients back)."""
+    x = np.asarray(x, np.float64)
+    d = x.shape[-1]
+    if d % 2:
+        raise ValueError("head dimension must be even")
+    half = d // 2
+    inv_freq = np.asarray(base, np.float64) ** (-2.0 * np.arange(half) / d)
+    ang = np.asarray(pos, np.float64)[..., None] * inv_freq          # [..., rows, half]
+    if inverse:
+        ang = -ang
+    cs, sn = np.cos(ang), np.sin(ang)
+    lo, hi = x[..., :half], x[..., half:]
+    return np.concatenate([lo * cs - hi * sn, hi * cs + lo * sn], axis=-1)
+
+
 # --------------------------------------------------------------------------
 # GetMask(j, k): the c x c tile of the causal mask seen by a ring step
 # --------------------------------------------------------------------------
