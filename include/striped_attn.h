@@ -82,6 +82,20 @@ int sa_unstripe_permute(const void* src, void* dst, int64_t outer, int64_t n_seq
                         int64_t inner_bytes, int32_t N, void* stream);
 
 /*
+ * Rotary position embedding with explicit position ids.  Sec. 2.3: when the tokens are
+ * stripe-permuted the position ids are permuted with them (the same sa_stripe_permute call on
+ * the id array), so that row a of device dev keeps the id a * N + dev of its original place.
+ * y[b, h, r, :] = x[b, h, r, :] with every pair (x_i, x_{i + d/2}), i < d/2, rotated by the
+ * angle pos[b, r] * base^(-2 i / d) (by the negative angle if inverse != 0: the transpose,
+ * which takes gradients back).  x and y have `shape`'s dtype and strides, shape->c rows; y
+ * may be x.  pos: device int32 [B, c], batches pos_stride_b elements apart (0: one id row
+ * shared by all batches).  Angles are formed in double precision.
+ * Errors: NULL, SHAPE (as sa_shape, or base <= 1, or 0 < pos_stride_b < c), ALIGN.
+ */
+int sa_rope(const void* x, void* y, const int32_t* pos, int64_t pos_stride_b, const sa_shape* shape,
+            float base, int32_t inverse, void* stream);
+
+/*
  * Initialise a device's output accumulator (Algorithm 1, first line): O = 0,
  * LSE = -inf.  o is fp32 [B, H, c, d], lse fp32 [B, H, c], strides from `shape`.
  */

@@ -46,6 +46,7 @@ def lib():
             "sa_stripe_permute": (i32, [vp, vp, i64, i64, i64, i32, vp]),
             "sa_unstripe_permute": (i32, [vp, vp, i64, i64, i64, i32, vp]),
             "sa_state_init": (i32, [vp, vp, shp, vp]),
+            "sa_rope": (i32, [vp, vp, vp, i64, shp, ctypes.c_float, i32, vp]),
             "sa_attn_step_fwd": (i32, [vp, vp, vp, vp, vp, i32, i32, i32, i32, shp, vp]),
             "sa_finalize": (i32, [vp, vp, shp, vp]),
             "sa_bwd_preprocess": (i32, [vp, vp, vp, shp, vp]),
@@ -69,7 +70,7 @@ def lib():
     return _lib
 
 
-EXPORTS = ("sa_stripe_permute", "sa_unstripe_permute", "sa_state_init", "sa_attn_step_fwd",
+EXPORTS = ("sa_stripe_permute", "sa_unstripe_permute", "sa_rope", "sa_state_init", "sa_attn_step_fwd",
            "sa_finalize", "sa_bwd_preprocess", "sa_attn_step_bwd", "sa_ring_fwd", "sa_ring_bwd",
            "sa_attn_step_fwd_tiled", "sa_attn_step_bwd_tiled", "sa_ring_fwd_tiled", "sa_ring_bwd_tiled",
            "sa_step_tiles", "sa_step_mask", "sa_step_pairs", "sa_status_str")
@@ -131,6 +132,15 @@ def _permute(name, src, dst, N, seq_axis):
     inner = math.prod(src.shape[seq_axis + 1:]) * src.element_size()
     _check(getattr(lib(), name)(_ptr(src), _ptr(dst), outer, src.shape[seq_axis], inner, N, _stream()),
            name)
+
+
+def sa_rope(x, y, pos, shape, base=10000.0, inverse=False):
+    """y <- x with rows rotated by their position ids pos (int32 [c] or [B, c], on the GPU)."""
+    if pos.dtype != torch.int32 or not pos.is_contiguous():
+        raise TypeError("pos must be a contiguous int32 tensor")
+    stride_b = pos.stride(0) if pos.dim() == 2 else 0
+    _check(lib().sa_rope(_ptr(x), _ptr(y), _ptr(pos), stride_b, ctypes.byref(shape), float(base),
+                         1 if inverse else 0, _stream()), "sa_rope")
 
 
 def sa_state_init(o, lse, shape):

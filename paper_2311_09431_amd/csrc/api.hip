@@ -176,6 +176,16 @@ int sa_state_init(float* o, float* lse, const sa_shape* shape, void* stream) {
     return sa::launch_state_init(o, lse, *shape, (hipStream_t)stream) == hipSuccess ? SA_OK : SA_ERR_HIP;
 }
 
+int sa_rope(const void* x, void* y, const int32_t* pos, int64_t pos_stride_b, const sa_shape* shape,
+            float base, int32_t inverse, void* stream) {
+    if (!x || !y || !pos) return SA_ERR_NULL;
+    if (int e = check_shape(shape)) return e;
+    if (pos_stride_b < 0 || (pos_stride_b > 0 && pos_stride_b < shape->c) || !(base > 1.f)) return SA_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(y) || (reinterpret_cast<uintptr_t>(pos) & 3u)) return SA_ERR_ALIGN;
+    return sa::launch_rope(x, y, pos, pos_stride_b, *shape, base, inverse != 0, (hipStream_t)stream) ==
+                   hipSuccess ? SA_OK : SA_ERR_HIP;
+}
+
 int sa_attn_step_fwd_tiled(const void* q, const void* k, const void* v, float* o, float* lse,
                            int32_t q_dev, int32_t kv_dev, int32_t N, int32_t layout, const sa_shape* shape,
                            int32_t skip_bq, int32_t skip_bk, void* stream) {

@@ -144,4 +144,72 @@ hipError_t launch_bwd_preprocess(const float* o, const void* dout, float* delta,
     return hipGetLastError();
 }
 
+// Rotary position embedding with explicit position ids (Sec. 2.3: with the striped layout the
+// ids are permuted together with the tokens, so row a of device dev carries id a N + dev).
+// A thread owns two neighbouring pairs (x_i, x_{i+d/2}) of one row and keeps their sines and
+// cosines, computed in double precision (ids reach 10^6, where an fp32 angle is off by 0.05
+// rad), across all heads (and batches, when they share the ids).
+template <typename T>
+__device__ inline float2 ld2(const T* p);
+template <>
+__device__ inline float2 ld2<float>(const float* p) { return *reinterpret_cast<const float2*>(p); }
+template <>
+__device__ inline float2 ld2<__hip_bfloat16>(const __hip_bfloat16* p) {
+    const uint32_t raw = *reinterpret_cast<const uint32_t*>(p);
+    return make_float2(__uint_as_float(raw << 16), __uint_as_float(raw & 0xffff0000u));
+}
+template <typename T>
+__device__ inline void st2(T* p, float2 v);
+template <>
+__device__ inline void st2<float>(float* p, float2 v) { *reinterpret_cast<float2*>(p) = v; }
+template <>
+__device__ inline void st2<__hip_bfloat16>(__hip_bfloat16* p, float2 v) {
+    __hip_bfloat16 t[2] = {__float2bfloat16(v.x), __float2bfloat16(v.y)};
+    *reinterpret_cast<uint32_t*>(p) = *reinterpret_cast<uint32_t*>(t);
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256)
+rope_kernel(const T* __restrict__ x, T* __restrict__ y, const int32_t* __restrict__ pos, int64_t pos_sb,
+            int B, int H, int c, int d, int64_t sb, int64_t sh, int64_t ss, double log2_base, bool inverse) {
+    const int half = d / 2, per_row = half / 2;          // two pairs per thread
+    const int64_t total = (int64_t)c * per_row;
+    for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * 256) {
+        const int64_t row = idx / per_row;
+        const int i = 2 * (int)(idx - row * per_row);
+        const double f0 = exp2(-2.0 * i / d * log2_base), f1 = exp2(-2.0 * (i + 1) / d * log2_base);
+        double s0 = 0., c0 = 1., s1 = 0., c1 = 1.;
+        for (int b = 0; b < B; ++b) {
+            if (b == 0 || pos_sb != 0) {
+                const double p = (double)pos[b * pos_sb + row];
+                sincos(p * f0, &s0, &c0);
+                sincos(p * f1, &s1, &c1);
+                if (inverse) { s0 = -s0; s1 = -s1; }
+            }
+            const float cf0 = (float)c0, sf0 = (float)s0, cf1 = (float)c1, sf1 = (float)s1;
+            for (int h = 0; h < H; ++h) {
+                const int64_t at = b * sb + h * sh + row * ss + i;
+                const float2 lo = ld2<T>(x + at), hi = ld2<T>(x + at + half);
+                st2<T>(y + at, make_float2(lo.x * cf0 - hi.x * sf0, lo.y * cf1 - hi.y * sf1));
+                st2<T>(y + at + half, make_float2(hi.x * cf0 + lo.x * sf0, hi.y * cf1 + lo.y * sf1));
+            }
+        }
+    }
+}
+
+hipError_t launch_rope(const void* x, void* y, const int32_t* pos, int64_t pos_stride_b, const sa_shape& s,
+                       float base, bool inverse, hipStream_t st) {
+    const int64_t total = (int64_t)s.c * (s.d / 4);
+    dim3 grid(row_blocks(total));
+    const double l2b = log2((double)base);
+    if (s.dtype == SA_F32)
+        hipLaunchKernelGGL(rope_kernel<float>, grid, dim3(256), 0, st, (const float*)x, (float*)y, pos,
+                           pos_stride_b, s.B, s.H, s.c, s.d, s.stride_b, s.stride_h, row_stride(s), l2b, inverse);
+    else
+        hipLaunchKernelGGL(rope_kernel<__hip_bfloat16>, grid, dim3(256), 0, st, (const __hip_bfloat16*)x,
+                           (__hip_bfloat16*)y, pos, pos_stride_b, s.B, s.H, s.c, s.d, s.stride_b, s.stride_h,
+                           row_stride(s), l2b, inverse);
+    return hipGetLastError();
+}
+
 }  // namespace sa

@@ -44,6 +44,8 @@ hipError_t launch_finalize(const float* o, void* out, const sa_shape& s, hipStre
 hipError_t launch_bwd_preprocess(const float* o, const void* dout, float* delta,
                                  const sa_shape& s, hipStream_t st);
 hipError_t launch_zero_f32(float* p, const sa_shape& s, hipStream_t st);
+hipError_t launch_rope(const void* x, void* y, const int32_t* pos, int64_t pos_stride_b, const sa_shape& s,
+                       float base, bool inverse, hipStream_t st);
 
 hipError_t launch_fwd_generic(const StepArgs& a, int dtype, hipStream_t st);
 hipError_t launch_bwd_generic(const StepArgs& a, int dtype, hipStream_t st);

@@ -155,3 +155,16 @@ def test_step_tiles_errors():
     assert L.sa_step_tiles(0, 5, 2, 1, 8, 4, 4, ctypes.byref(a), ctypes.byref(b)) == -3
     assert L.sa_step_tiles(0, 0, 2, 7, 8, 4, 4, ctypes.byref(a), ctypes.byref(b)) == -5
     assert L.sa_step_tiles(0, 0, 2, 1, 8, 4, 4, None, ctypes.byref(b)) == -1
+
+
+def test_rope_argument_errors():
+    L = sa.lib()
+    p = ctypes.c_void_p(0x1000)
+    ok = _shape()
+    f = L.sa_rope
+    assert f(None, p, p, 0, ctypes.byref(ok), 10000.0, 0, None) == -1
+    assert f(p, p, None, 0, ctypes.byref(ok), 10000.0, 0, None) == -1
+    assert f(p, p, p, 0, ctypes.byref(ok), 1.0, 0, None) == -2          # base must exceed 1
+    assert f(p, p, p, 3, ctypes.byref(ok), 10000.0, 0, None) == -2      # id rows would overlap
+    assert f(p, p, ctypes.c_void_p(0x1002), 0, ctypes.byref(ok), 10000.0, 0, None) == -6
+    assert f(p, p, p, 0, ctypes.byref(_shape(d=0)), 10000.0, 0, None) == -2
