@@ -21,7 +21,9 @@ N devices, block size c = n_seq / N, query device j, key/value device k.
 Pinned by tests/test_oracle_*.py against: brute-force S x S softmax with the
 mask matrix C, closed forms (Q = 0, V = 1, first row), a library causal SDPA
 and library autograd in fp64, central finite differences, the paper's printed
-stripe example, its Work(i, j) formula and its tiling examples.
+stripe example, its Work(i, j) formula and its tiling examples; the grouped-head
+functions (fewer key/value heads, an extension) against the library's grouped
+attention and autograd, repeated heads and finite differences.
 """
 import numpy as np
 
@@ -115,6 +117,48 @@ def causal_attention_grad_bh(Q, K, V, dO, scale, rows=None):
     """causal_attention_grad over leading [B, H] axes."""
     return _map_bh(lambda q, k, v, g: causal_attention_grad(q, k, v, g, scale, rows),
                    3, Q, K, V, dO)
+
+
+# --------------------------------------------------------------------------
+# Fewer key/value heads than query heads (grouped-query / multi-query attention).
+# Not part of the paper: each query head is the attention of Sec. 2.1 against the
+# key/value head its group shares, so the oracle is that definition per query
+# head, and a shared head's gradient is the sum over the query heads that read it.
+# --------------------------------------------------------------------------
+def kv_head_of(h, H, H_kv):
+    """Key/value head read by query head h: consecutive groups of H / H_kv query heads."""
+    assert H % H_kv == 0
+    return h // (H // H_kv)
+
+
+def causal_attention_gqa(Q, K, V, scale):
+    """Q [B, H, S, d], K and V [B, H_kv, S, d] -> (O [B, H, S, d], LSE [B, H, S])."""
+    B, H = Q.shape[:2]
+    H_kv = K.shape[1]
+    O = np.zeros(Q.shape)
+    LSE = np.zeros(Q.shape[:3])
+    for b in range(B):
+        for h in range(H):
+            hk = kv_head_of(h, H, H_kv)
+            O[b, h], LSE[b, h] = causal_attention(Q[b, h], K[b, hk], V[b, hk], scale)
+    return O, LSE
+
+
+def causal_attention_gqa_grad(Q, K, V, dO, scale):
+    """Gradient of sum(O * dO) for causal_attention_gqa: dQ like Q, dK and dV like K, V."""
+    B, H = Q.shape[:2]
+    H_kv = K.shape[1]
+    dQ = np.zeros(Q.shape)
+    dK = np.zeros(K.shape)
+    dV = np.zeros(V.shape)
+    for b in range(B):
+        for h in range(H):
+            hk = kv_head_of(h, H, H_kv)
+            q, k, v = causal_attention_grad(Q[b, h], K[b, hk], V[b, hk], dO[b, h], scale)
+            dQ[b, h] = q
+            dK[b, hk] += k
+            dV[b, hk] += v
+    return dQ, dK, dV
 
 
 # --------------------------------------------------------------------------
