@@ -81,17 +81,19 @@ class Runner:
         B, H, S, d, N = w["B"], w["H"], w["S"], w["d"], w["N"]
         dev = "cuda"
         n_in = 4 if bwd else 3
-        self.orig = [inputs.gaussian((B, H, S, d), seed * 16 + i, torch.bfloat16, device=dev)
-                     for i in range(n_in)]
+        hkv = w.get("H_kv", H)           # K and V (inputs 1 and 2) may have fewer heads
+        self.orig = [inputs.gaussian((B, hkv if i in (1, 2) else H, S, d), seed * 16 + i, torch.bfloat16,
+                                     device=dev) for i in range(n_in)]
         self.perm = [torch.empty_like(x) for x in self.orig]
         self.O = torch.empty(B, H, S, d, dtype=torch.float32, device=dev)
         self.LSE = torch.empty(B, H, S, dtype=torch.float32, device=dev)
         self.out = torch.empty(B, H, S, d, dtype=torch.bfloat16, device=dev)
         self.c = S // N
-        self.shape = sa.shard_shape(self.orig[0], self.c, self.LSE)
+        self.shape = sa.shard_shape(self.orig[0], self.c, self.LSE, kv=self.orig[1] if hkv != H else None)
         if bwd:
             self.delta = torch.empty_like(self.LSE)
-            self.dQ, self.dK, self.dV = (torch.empty_like(self.O) for _ in range(3))
+            self.dQ = torch.empty_like(self.O)
+            self.dK, self.dV = (torch.empty(B, hkv, S, d, dtype=torch.float32, device=dev) for _ in range(2))
 
     def one_pass(self, layout, timed):
         """The hot path for the played device(s).  Returns per-step ms tables or None."""
@@ -205,6 +207,9 @@ def main():
     ap.add_argument("--skip-granularity", default="", metavar="BQxBK",
                     help="emulate tile skipping per BQ x BK tile (Sec. 3.1 of the paper), e.g. 2048x4096; "
                          "default: the kernels' own 32 x 32")
+    ap.add_argument("--kv-heads", type=int, default=0, metavar="H_KV",
+                    help="K and V with H_KV heads shared by groups of query heads (an extension; "
+                         "default: as many as query heads, the paper's models)")
     args = ap.parse_args()
     skip = tuple(int(x) for x in args.skip_granularity.lower().split("x")) if args.skip_granularity else (0, 0)
     if len(skip) != 2:
@@ -217,7 +222,12 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     sa.lib()
-    w = WORKLOADS[args.workload]
+    w = dict(WORKLOADS[args.workload])
+    if args.kv_heads:
+        if args.kv_heads < 1 or w["H"] % args.kv_heads:
+            ap.error("--kv-heads must divide the workload's %d heads" % w["H"])
+        w["H_kv"] = args.kv_heads
+        w["desc"] += ", %d key/value heads" % args.kv_heads
     run = Runner(w, args.seed, bool(args.bwd), skip)
     torch.cuda.synchronize()
 
@@ -259,7 +269,7 @@ def main():
         tot_ms = sum(r["ms"] for r in live)
         ach = sum(r["tflops"] * r["ms"] for r in live) / max(1e-9, tot_ms)
         return dict(bound="mfma", kernel=name, achieved=round(ach, 1), peak=PEAK_BF16_TFLOPS,
-                    unit="TFLOP/s", frac=round(ach / PEAK_BF16_TFLOPS, 4), **traffic_fields(args.workload, name),
+                    unit="TFLOP/s", frac=round(ach / PEAK_BF16_TFLOPS, 4), **traffic_fields("" if args.kv_heads else args.workload, name),
                     avg_launch_ms=round(tot_ms / max(1, len(live)), 4), total_ms=round(tot_ms, 3))
     roofs = {"fwd": roof(striped_rows, "fwd ring step (fwd_mfma_kernel)")}
     if args.bwd:
@@ -272,7 +282,8 @@ def main():
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": args.workload + ": " + w["desc"], "B": w["B"], "H": w["H"], "d": w["d"],
+        "config": {"workload": args.workload + ": " + w["desc"], "B": w["B"], "H": w["H"],
+                   "H_kv": w.get("H_kv", w["H"]), "d": w["d"],
                    "n_seq": w["S"], "N": N, "c": w["S"] // N, "q_dev": w["q_dev"],
                    "pass": "stripe_permute + ring fwd" + (" + ring bwd" if args.bwd else "") + " + finalize"},
         "frac_of_bf16_peak": round(value / PEAK_BF16_TFLOPS, 4),

@@ -62,6 +62,17 @@ typedef struct {
     int64_t stat_stride_h; /* elements between heads in LSE / delta */
     int32_t dtype;         /* sa_dtype of Q/K/V/dO (O, LSE, delta, dQ, dK, dV are fp32) */
     float softmax_scale;   /* multiplies q.k inside the softmax; <= 0 selects 1/sqrt(d) */
+    /* Fewer key/value heads than query heads (grouped-query and multi-query attention; an
+       extension, the paper's models have H_kv = H).  H_kv = 0 means H, and then K, V, dK, dV
+       have the strides above and the three fields below are not looked at.  H_kv > 0 must
+       divide H; query head h reads key/value head h / (H / H_kv), and K, V, dK, dV are
+       [B, H_kv, c, d]-shaped with the strides below, under the same rules as stride_b,
+       stride_h, stride_s (with H_kv for H).  Q, dO, O, dQ, LSE and delta keep H heads and the
+       strides above.  Only the step and ring entry points look at these fields. */
+    int32_t H_kv;
+    int64_t kv_stride_b;
+    int64_t kv_stride_h;
+    int64_t kv_stride_s;   /* 0 selects d */
 } sa_shape;
 
 /*

@@ -23,7 +23,9 @@ class SaShape(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("c", ctypes.c_int32),
                 ("d", ctypes.c_int32), ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64),
                 ("stride_s", ctypes.c_int64), ("stat_stride_b", ctypes.c_int64), ("stat_stride_h", ctypes.c_int64),
-                ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float)]
+                ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
+                ("H_kv", ctypes.c_int32), ("kv_stride_b", ctypes.c_int64), ("kv_stride_h", ctypes.c_int64),
+                ("kv_stride_s", ctypes.c_int64)]
 
 
 class StripedAttnError(RuntimeError):
@@ -99,15 +101,23 @@ def _dtype_code(t):
     raise TypeError("Q/K/V must be float32 or bfloat16")
 
 
-def shard_shape(x, c, lse=None, scale=None):
+def shard_shape(x, c, lse=None, scale=None, kv=None):
     """sa_shape of a c-row shard of x indexed [B, H, rows, d] (d contiguous; any batch, head
-    and row strides, e.g. a [B, rows, H, d] tensor viewed through permute(0, 2, 1, 3))."""
+    and row strides, e.g. a [B, rows, H, d] tensor viewed through permute(0, 2, 1, 3)).
+    kv: a key/value tensor [B, H_kv, rows, d] when K, V, dK, dV have fewer heads than x or
+    strides of their own (all four must share them)."""
     B, H, rows, d = x.shape
     if x.stride(3) != 1:
         raise ValueError("the head dimension must be contiguous")
     ssb, ssh = (lse.stride(0), lse.stride(1)) if lse is not None else (H * rows, rows)
-    return SaShape(B, H, c, d, x.stride(0), x.stride(1), x.stride(2), ssb, ssh, _dtype_code(x),
-                   float(scale) if scale else 0.0)
+    shape = SaShape(B, H, c, d, x.stride(0), x.stride(1), x.stride(2), ssb, ssh, _dtype_code(x),
+                    float(scale) if scale else 0.0)
+    if kv is not None:
+        if kv.shape[0] != B or kv.shape[3] != d or kv.stride(3) != 1:
+            raise ValueError("K/V must be [B, H_kv, rows, d] with the head dimension contiguous")
+        shape.H_kv, shape.kv_stride_b, shape.kv_stride_h, shape.kv_stride_s = (
+            kv.shape[1], kv.stride(0), kv.stride(1), kv.stride(2))
+    return shape
 
 
 def _rows(t, dev, c):

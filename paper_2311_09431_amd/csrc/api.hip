@@ -14,34 +14,48 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 inline int64_t row_stride(const sa_shape* s) { return s->stride_s > 0 ? s->stride_s : s->d; }
 
+// strides of one [B, heads, rows, d]-like tensor family
+struct Geom { int heads; int64_t sb, sh, ss; };
+inline Geom q_geom(const sa_shape* s) { return {s->H, s->stride_b, s->stride_h, row_stride(s)}; }
+inline bool grouped(const sa_shape* s) { return s->H_kv > 0; }
+inline Geom kv_geom(const sa_shape* s) {
+    if (!grouped(s)) return q_geom(s);
+    return {s->H_kv, s->kv_stride_b, s->kv_stride_h, s->kv_stride_s > 0 ? s->kv_stride_s : s->d};
+}
+
+// rows rows per (batch, head) must not overlap each other
+int check_geom(const Geom& g, int B, int64_t rows, int d) {
+    const int dmul = 4;      // rows are read four elements at a time (16 or 8 bytes)
+    if (g.ss < d) return SA_ERR_SHAPE;
+    // heads apart ([B, H, rows, d]-like) or interleaved within a row step ([B, rows, H, d]-like)
+    const bool heads_apart = g.sh >= rows * g.ss;
+    const bool heads_inside = g.sh >= d && g.ss >= (int64_t)g.heads * g.sh;
+    if (!heads_apart && !heads_inside) return SA_ERR_SHAPE;
+    if (B > 1 && g.sb < (heads_apart ? g.sh : rows * g.ss)) return SA_ERR_SHAPE;
+    if (g.sb % dmul || g.sh % dmul || g.ss % dmul) return SA_ERR_ALIGN;
+    return SA_OK;
+}
+
 int check_shape(const sa_shape* s) {
     if (!s) return SA_ERR_NULL;
     if (s->dtype != SA_F32 && s->dtype != SA_BF16) return SA_ERR_DTYPE;
     if (s->B < 1 || s->H < 1 || s->c < 1 || s->d < 1 || s->d > 256) return SA_ERR_SHAPE;
     if ((int64_t)s->B * s->H > 65535) return SA_ERR_SHAPE;
-    const int dmul = 4;      // rows are read four elements at a time (16 or 8 bytes)
-    if (s->d % dmul) return SA_ERR_SHAPE;
-    const int64_t ss = row_stride(s);
-    if (ss < s->d || s->stat_stride_h < s->c) return SA_ERR_SHAPE;
-    // heads apart ([B, H, rows, d]-like) or interleaved within a row step ([B, rows, H, d]-like)
-    const bool heads_apart = s->stride_h >= (int64_t)s->c * ss;
-    const bool heads_inside = s->stride_h >= s->d && ss >= (int64_t)s->H * s->stride_h;
-    if (!heads_apart && !heads_inside) return SA_ERR_SHAPE;
-    if (s->B > 1 && (s->stride_b < (heads_apart ? s->stride_h : (int64_t)s->c * ss) ||
-                     s->stat_stride_b < s->stat_stride_h))
-        return SA_ERR_SHAPE;
-    if (s->stride_b % dmul || s->stride_h % dmul || ss % dmul) return SA_ERR_ALIGN;
+    if (s->d % 4) return SA_ERR_SHAPE;
+    if (s->H_kv < 0 || (grouped(s) && s->H % s->H_kv)) return SA_ERR_SHAPE;
+    if (s->stat_stride_h < s->c || (s->B > 1 && s->stat_stride_b < s->stat_stride_h)) return SA_ERR_SHAPE;
+    if (int e = check_geom(q_geom(s), s->B, s->c, s->d)) return e;
+    if (grouped(s))
+        if (int e = check_geom(kv_geom(s), s->B, s->c, s->d)) return e;
     return SA_OK;
 }
 
 // the ring drivers address N shards of c rows inside the same tensors
 int check_ring_extent(const sa_shape* s, int N) {
-    const int64_t ss = row_stride(s), rows = (int64_t)N * s->c;
-    const bool heads_apart = s->stride_h >= rows * ss;
-    const bool heads_inside = s->stride_h >= s->d && ss >= (int64_t)s->H * s->stride_h;
-    if (!heads_apart && !heads_inside) return SA_ERR_SHAPE;
-    if (s->B > 1 && !heads_apart && s->stride_b < rows * ss) return SA_ERR_SHAPE;
+    const int64_t rows = (int64_t)N * s->c;
     if (s->stat_stride_h < rows) return SA_ERR_SHAPE;
+    if (check_geom(q_geom(s), s->B, rows, s->d) || check_geom(kv_geom(s), s->B, rows, s->d))
+        return SA_ERR_SHAPE;
     return SA_OK;
 }
 
@@ -70,6 +84,8 @@ StepArgs make_args(const sa_shape* s) {
     a.stride_b = s->stride_b; a.stride_h = s->stride_h;
     a.stat_stride_b = s->stat_stride_b; a.stat_stride_h = s->stat_stride_h;
     a.stride_s = row_stride(s);
+    const Geom kv = kv_geom(s);
+    a.H_kv = kv.heads; a.kv_stride_b = kv.sb; a.kv_stride_h = kv.sh; a.kv_stride_s = kv.ss;
     a.scale = s->softmax_scale > 0.f ? s->softmax_scale : 1.0f / sqrtf((float)s->d);
     return a;
 }
@@ -253,7 +269,9 @@ int sa_ring_fwd_tiled(const void* Q, const void* K, const void* V, float* O, flo
     hipStream_t st = (hipStream_t)stream;
     const size_t es = elt_size(shape->dtype);
     const int64_t shard = (int64_t)shape->c * row_stride(shape);     // elements between shards
+    const int64_t kv_shard = (int64_t)shape->c * kv_geom(shape).ss;  // ... of K and V
     auto in_at = [&](const void* p, int dev) { return (const char*)p + (size_t)dev * shard * es; };
+    auto kv_at = [&](const void* p, int dev) { return (const char*)p + (size_t)dev * kv_shard * es; };
     if (step_ms) for (int i = 0; i < N * N; ++i) step_ms[i] = 0.f;
     const int j0 = q_dev_only >= 0 ? q_dev_only : 0, j1 = q_dev_only >= 0 ? q_dev_only + 1 : N;
     for (int j = j0; j < j1; ++j)
@@ -264,7 +282,7 @@ int sa_ring_fwd_tiled(const void* Q, const void* K, const void* V, float* O, flo
         for (int j = j0; j < j1; ++j) {
             const int k = ((j - i) % N + N) % N;            // Algorithm 1: block held in round i
             if (!timer.begin(st, i * N + j)) return SA_ERR_HIP;
-            int e = step_fwd(in_at(Q, j), in_at(K, k), in_at(V, k), O + j * shard,
+            int e = step_fwd(in_at(Q, j), kv_at(K, k), kv_at(V, k), O + j * shard,
                              LSE + (int64_t)j * shape->c, j, k, layout, shape, skip_bq, skip_bk, st);
             if (e) return e;
             if (!timer.end(st)) return SA_ERR_HIP;
@@ -294,13 +312,18 @@ int sa_ring_bwd_tiled(const void* Q, const void* K, const void* V, const void* d
     hipStream_t st = (hipStream_t)stream;
     const size_t es = elt_size(shape->dtype);
     const int64_t shard = (int64_t)shape->c * row_stride(shape);     // elements between shards
+    const Geom kvg = kv_geom(shape);
+    const int64_t kv_shard = (int64_t)shape->c * kvg.ss;             // ... of K, V, dK, dV
     auto in_at = [&](const void* p, int dev) { return (const char*)p + (size_t)dev * shard * es; };
+    auto kv_at = [&](const void* p, int dev) { return (const char*)p + (size_t)dev * kv_shard * es; };
     if (step_ms) for (int i = 0; i < N * N; ++i) step_ms[i] = 0.f;
     const int j0 = q_dev_only >= 0 ? q_dev_only : 0, j1 = q_dev_only >= 0 ? q_dev_only + 1 : N;
+    sa_shape kv_shape = *shape;          // dK and dV as a tensor family of their own
+    kv_shape.H = kvg.heads; kv_shape.stride_b = kvg.sb; kv_shape.stride_h = kvg.sh; kv_shape.stride_s = kvg.ss;
     for (int dev = 0; dev < N; ++dev) {
         if (sa::launch_zero_f32(dQ + dev * shard, *shape, st) != hipSuccess ||
-            sa::launch_zero_f32(dK + dev * shard, *shape, st) != hipSuccess ||
-            sa::launch_zero_f32(dV + dev * shard, *shape, st) != hipSuccess)
+            sa::launch_zero_f32(dK + dev * kv_shard, kv_shape, st) != hipSuccess ||
+            sa::launch_zero_f32(dV + dev * kv_shard, kv_shape, st) != hipSuccess)
             return SA_ERR_HIP;
     }
     for (int j = j0; j < j1; ++j)
@@ -312,9 +335,10 @@ int sa_ring_bwd_tiled(const void* Q, const void* K, const void* V, const void* d
         for (int j = j0; j < j1; ++j) {
             const int k = ((j - i) % N + N) % N;
             if (!timer.begin(st, i * N + j)) return SA_ERR_HIP;
-            int e = step_bwd(in_at(Q, j), in_at(K, k), in_at(V, k), in_at(dO, j),
+            int e = step_bwd(in_at(Q, j), kv_at(K, k), kv_at(V, k), in_at(dO, j),
                              LSE + (int64_t)j * shape->c, delta + (int64_t)j * shape->c, dQ + j * shard,
-                             dK + k * shard, dV + k * shard, j, k, layout, shape, skip_bq, skip_bk, st);
+                             dK + k * kv_shard, dV + k * kv_shard, j, k, layout, shape, skip_bq, skip_bk,
+                             st);
             if (e) return e;
             if (!timer.end(st)) return SA_ERR_HIP;
         }

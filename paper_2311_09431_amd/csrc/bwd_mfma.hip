@@ -110,14 +110,16 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
     const int qt = TRI ? n_tiles - 1 - rank : rank;      // heaviest query tiles first
     const int b = bh / p.H, hd = bh - b * p.H;
     const int64_t base = b * p.stride_b + hd * p.stride_h;
+    // key/value head of this query head's group (the same head when H_kv == H)
+    const int64_t kv_base = b * p.kv_stride_b + (hd / (p.H / p.H_kv)) * p.kv_stride_h;
     const int64_t sbase = b * p.stat_stride_b + hd * p.stat_stride_h;
     const __bf16* Q = (const __bf16*)p.q + base;
     const int d = p.d;                                 // d <= 128, zero-padded to 128 columns
-    const int64_t ss = p.stride_s;                     // elements between consecutive rows
-    const int pitch = 2 * (int)ss;                     // bytes
+    const int64_t ss = p.stride_s;                     // elements between consecutive rows of Q, dO, dQ
+    const int pitch = 2 * (int)p.kv_stride_s;          // bytes between consecutive rows of K and V
     const int tile_pitch = DT_ROWS * pitch;            // bytes between 64-row tiles in global memory
-    const dt_rsrc Kr = dt_make_rsrc((const __bf16*)p.k + base, p.c, pitch, d);
-    const dt_rsrc Vr = dt_make_rsrc((const __bf16*)p.v + base, p.c, pitch, d);
+    const dt_rsrc Kr = dt_make_rsrc((const __bf16*)p.k + kv_base, p.c, pitch, d);
+    const dt_rsrc Vr = dt_make_rsrc((const __bf16*)p.v + kv_base, p.c, pitch, d);
     const __bf16* G = (const __bf16*)p.dout + base;
     float* DQ = p.dq + base;
 
@@ -344,22 +346,26 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
     const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, h = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform, kept scalar
     int ktile, bh;                                // triangular steps: low key tiles see most queries: first
-    decode_block<false>((int)blockIdx.x, n_tiles, p.B * p.H, ktile, bh);
-    const int b = bh / p.H, hd = bh - b * p.H;
+    // one workgroup per (key tile, batch, key/value head); the query head is this launch's
+    // member of the group that shares the key/value head
+    decode_block<false>((int)blockIdx.x, n_tiles, p.B * p.H_kv, ktile, bh);
+    const int b = bh / p.H_kv, kvh = bh - b * p.H_kv;
+    const int hd = kvh * (p.H / p.H_kv) + p.member;
     const int64_t base = b * p.stride_b + hd * p.stride_h;
+    const int64_t kv_base = b * p.kv_stride_b + kvh * p.kv_stride_h;
     const int64_t sbase = b * p.stat_stride_b + hd * p.stat_stride_h;
     const int d = p.d;                                 // d <= 128, zero-padded to 128 columns
-    const int64_t ss = p.stride_s;                     // elements between consecutive rows
-    const int pitch = 2 * (int)ss;                     // bytes
+    const int64_t ss = p.kv_stride_s;                  // elements between consecutive rows of K, V, dK, dV
+    const int pitch = 2 * (int)p.stride_s;             // bytes between consecutive rows of Q and dO
     const int tile_pitch = DT_ROWS * pitch;            // bytes between 64-row tiles in global memory
     const dt_rsrc Qr = dt_make_rsrc((const __bf16*)p.q + base, p.c, pitch, d);
     const dt_rsrc Gr = dt_make_rsrc((const __bf16*)p.dout + base, p.c, pitch, d);
-    const __bf16* K = (const __bf16*)p.k + base;
-    const __bf16* V = (const __bf16*)p.v + base;
+    const __bf16* K = (const __bf16*)p.k + kv_base;
+    const __bf16* V = (const __bf16*)p.v + kv_base;
     const float* LSE = p.lse + sbase;
     const float* DEL = p.delta + sbase;
-    float* DK = p.dk + base;
-    float* DV = p.dv + base;
+    float* DK = p.dk + kv_base;
+    float* DV = p.dv + kv_base;
 
     const int k0 = ktile * BM, key = k0 + 32 * wave + n;
     const int n_qt = p.c / DT_ROWS;
@@ -507,8 +513,9 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
 bool bwd_mfma_supported(const StepArgs& a, int dtype) {
     // the tile loads address a shard through a buffer descriptor with 32-bit byte offsets:
     // its last row must end below 2^31 bytes from its first
+    const int64_t widest = a.stride_s > a.kv_stride_s ? a.stride_s : a.kv_stride_s;
     return dtype == SA_BF16 && a.d <= D && a.d % 4 == 0 && a.c % BM == 0 &&
-           (int64_t)(a.c - 1) * 2 * a.stride_s + 2 * a.d < (int64_t(1) << 31);
+           (int64_t)(a.c - 1) * 2 * widest + 2 * a.d < (int64_t(1) << 31);
 }
 
 hipError_t launch_bwd_mfma(const StepArgs& a, hipStream_t st) {
@@ -518,12 +525,17 @@ hipError_t launch_bwd_mfma(const StepArgs& a, hipStream_t st) {
     else
         hipLaunchKernelGGL(bwd_dq_mfma_kernel<false>, dim3(n_tiles * a.B * a.H), dim3(256), 0, st, a, n_tiles);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    if (a.kind == MASK_TRI)
-        hipLaunchKernelGGL(bwd_dkdv_mfma_kernel<true>, dim3(n_tiles * a.B * a.H), dim3(256), 0, st, a, n_tiles);
-    else
-        hipLaunchKernelGGL(bwd_dkdv_mfma_kernel<false>, dim3(n_tiles * a.B * a.H), dim3(256), 0, st, a, n_tiles);
-    return hipGetLastError();
+    // dK, dV: the members of a group of query heads one after the other, each adding to the
+    // shared head's accumulators in stream order (deterministic)
+    StepArgs m = a;
+    for (m.member = 0; m.member < a.H / a.H_kv && e == hipSuccess; ++m.member) {
+        if (a.kind == MASK_TRI)
+            hipLaunchKernelGGL(bwd_dkdv_mfma_kernel<true>, dim3(n_tiles * a.B * a.H_kv), dim3(256), 0, st, m, n_tiles);
+        else
+            hipLaunchKernelGGL(bwd_dkdv_mfma_kernel<false>, dim3(n_tiles * a.B * a.H_kv), dim3(256), 0, st, m, n_tiles);
+        e = hipGetLastError();
+    }
+    return e;
 }
 
 }  // namespace sa

@@ -180,13 +180,15 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     const int qt = TRI ? n_qtiles - 1 - rank : rank;      // triangular steps: heaviest query tiles first
     const int b = bh / p.H, hd = bh - b * p.H;
     const int64_t base = b * p.stride_b + hd * p.stride_h;
+    // key/value head of this query head's group (the same head when H_kv == H)
+    const int64_t kv_base = b * p.kv_stride_b + (hd / (p.H / p.H_kv)) * p.kv_stride_h;
     const __bf16* Q = (const __bf16*)p.q + base;
     const int d = p.d;                                 // d <= 128, zero-padded to 128 columns
-    const int64_t ss = p.stride_s;                     // elements between consecutive rows
-    const int pitch = 2 * (int)ss;                     // bytes
+    const int64_t ss = p.stride_s;                     // elements between consecutive rows of Q and O
+    const int pitch = 2 * (int)p.kv_stride_s;          // bytes between consecutive rows of K and V
     const int tile_pitch = TILE_ROWS * pitch;          // bytes between 64-row tiles in global memory
-    const dt_rsrc K = dt_make_rsrc((const __bf16*)p.k + base, p.c, pitch, d);
-    const dt_rsrc V = dt_make_rsrc((const __bf16*)p.v + base, p.c, pitch, d);
+    const dt_rsrc K = dt_make_rsrc((const __bf16*)p.k + kv_base, p.c, pitch, d);
+    const dt_rsrc V = dt_make_rsrc((const __bf16*)p.v + kv_base, p.c, pitch, d);
     float* O = p.o + base;
     float* L = p.lse + b * p.stat_stride_b + hd * p.stat_stride_h;
 
@@ -367,7 +369,7 @@ bool fwd_mfma_supported(const StepArgs& a, int dtype) {
     // the tile loads address a shard through a buffer descriptor with 32-bit byte offsets:
     // its last row must end below 2^31 bytes from its first
     return dtype == SA_BF16 && a.d <= D && a.d % 4 == 0 && a.c % BM == 0 &&
-           (int64_t)(a.c - 1) * 2 * a.stride_s + 2 * a.d < (int64_t(1) << 31);
+           (int64_t)(a.c - 1) * 2 * a.kv_stride_s + 2 * a.d < (int64_t(1) << 31);
 }
 
 hipError_t launch_fwd_mfma(const StepArgs& a, hipStream_t st) {

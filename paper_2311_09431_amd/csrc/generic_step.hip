@@ -63,13 +63,16 @@ fwd_generic_kernel(StepArgs p) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int bh = blockIdx.y, b = bh / p.H, h = bh - b * p.H;
     const int64_t base = b * p.stride_b + h * p.stride_h;
+    // key/value head of this query head's group (the same head when H_kv == H)
+    const int64_t kv_base = b * p.kv_stride_b + (h / (p.H / p.H_kv)) * p.kv_stride_h;
     const T* Q = (const T*)p.q + base;
-    const T* K = (const T*)p.k + base;
-    const T* V = (const T*)p.v + base;
+    const T* K = (const T*)p.k + kv_base;
+    const T* V = (const T*)p.v + kv_base;
     float* O = p.o + base;
     float* L = p.lse + b * p.stat_stride_b + h * p.stat_stride_h;
     const int d = p.d;
-    const int64_t ss = p.stride_s;        // elements between consecutive rows
+    const int64_t ss = p.stride_s;        // elements between consecutive rows of Q and O
+    const int64_t ks = p.kv_stride_s;     // ... of K and V
 
     for (int r = 0; r < kRowsPerWave; ++r) {
         const int a = (blockIdx.x * kWaves + wave) * kRowsPerWave + r;
@@ -90,7 +93,7 @@ fwd_generic_kernel(StepArgs p) {
         for (int b0 = 0; b0 < nkeys; b0 += 64) {
             const int key = b0 + lane;
             const bool valid = key < nkeys;
-            float s = valid ? p.scale * dot_row<T>(q_lds[wave], K + (int64_t)key * ss, d) : -INFINITY;
+            float s = valid ? p.scale * dot_row<T>(q_lds[wave], K + (int64_t)key * ks, d) : -INFINITY;
             const float m_new = fmaxf(m, wave_max(s));        // finite: lane 0 is always valid
             const float alpha = (m == -INFINITY) ? 0.f : expf(m - m_new);
             const float pr = valid ? expf(s - m_new) : 0.f;
@@ -100,7 +103,7 @@ fwd_generic_kernel(StepArgs p) {
             const int nk = min(64, nkeys - b0);
             for (int kk = 0; kk < nk; ++kk) {
                 const float pk = __shfl(pr, kk);
-                const T* vrow = V + (int64_t)(b0 + kk) * ss;
+                const T* vrow = V + (int64_t)(b0 + kk) * ks;
 #pragma unroll
                 for (int i = 0; i < kMaxD / 64; ++i) {
                     const int t = lane + 64 * i;
@@ -129,15 +132,17 @@ bwd_dq_generic_kernel(StepArgs p) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int bh = blockIdx.y, b = bh / p.H, h = bh - b * p.H;
     const int64_t base = b * p.stride_b + h * p.stride_h;
+    const int64_t kv_base = b * p.kv_stride_b + (h / (p.H / p.H_kv)) * p.kv_stride_h;
     const T* Q = (const T*)p.q + base;
-    const T* K = (const T*)p.k + base;
-    const T* V = (const T*)p.v + base;
+    const T* K = (const T*)p.k + kv_base;
+    const T* V = (const T*)p.v + kv_base;
     const T* G = (const T*)p.dout + base;
     float* DQ = p.dq + base;
     const float* L = p.lse + b * p.stat_stride_b + h * p.stat_stride_h;
     const float* D = p.delta + b * p.stat_stride_b + h * p.stat_stride_h;
     const int d = p.d;
-    const int64_t ss = p.stride_s;        // elements between consecutive rows
+    const int64_t ss = p.stride_s;        // elements between consecutive rows of Q, dO, dQ
+    const int64_t ks = p.kv_stride_s;     // ... of K and V
 
     for (int r = 0; r < kRowsPerWave; ++r) {
         const int a = (blockIdx.x * kWaves + wave) * kRowsPerWave + r;
@@ -157,15 +162,15 @@ bwd_dq_generic_kernel(StepArgs p) {
             const int key = b0 + lane;
             float ds = 0.f;
             if (key < nkeys) {
-                const float s = p.scale * dot_row<T>(q_lds[wave], K + (int64_t)key * ss, d);
+                const float s = p.scale * dot_row<T>(q_lds[wave], K + (int64_t)key * ks, d);
                 const float pr = expf(s - lse);
-                const float dp = dot_row<T>(g_lds[wave], V + (int64_t)key * ss, d);
+                const float dp = dot_row<T>(g_lds[wave], V + (int64_t)key * ks, d);
                 ds = pr * (dp - delta);
             }
             const int nk = min(64, nkeys - b0);
             for (int kk = 0; kk < nk; ++kk) {
                 const float x = __shfl(ds, kk);
-                const T* krow = K + (int64_t)(b0 + kk) * ss;
+                const T* krow = K + (int64_t)(b0 + kk) * ks;
 #pragma unroll
                 for (int i = 0; i < kMaxD / 64; ++i) {
                     const int t = lane + 64 * i;
@@ -182,25 +187,24 @@ bwd_dq_generic_kernel(StepArgs p) {
     }
 }
 
-// dK, dV: one wave per key row, lanes over the queries that may see it.
+// dK, dV: one wave per key row, lanes over the queries that may see it, the query heads of
+// the group that shares the key/value head one after the other.
 template <typename T>
 __global__ void __launch_bounds__(kWaves * 64)
 bwd_dkv_generic_kernel(StepArgs p) {
     __shared__ float k_lds[kWaves][kMaxD];
     __shared__ float v_lds[kWaves][kMaxD];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int bh = blockIdx.y, b = bh / p.H, h = bh - b * p.H;
-    const int64_t base = b * p.stride_b + h * p.stride_h;
-    const T* Q = (const T*)p.q + base;
-    const T* K = (const T*)p.k + base;
-    const T* V = (const T*)p.v + base;
-    const T* G = (const T*)p.dout + base;
-    float* DK = p.dk + base;
-    float* DV = p.dv + base;
-    const float* L = p.lse + b * p.stat_stride_b + h * p.stat_stride_h;
-    const float* D = p.delta + b * p.stat_stride_b + h * p.stat_stride_h;
+    const int bh = blockIdx.y, b = bh / p.H_kv, kvh = bh - b * p.H_kv;
+    const int group = p.H / p.H_kv;
+    const int64_t kv_base = b * p.kv_stride_b + kvh * p.kv_stride_h;
+    const T* K = (const T*)p.k + kv_base;
+    const T* V = (const T*)p.v + kv_base;
+    float* DK = p.dk + kv_base;
+    float* DV = p.dv + kv_base;
     const int d = p.d;
-    const int64_t ss = p.stride_s;        // elements between consecutive rows
+    const int64_t ss = p.stride_s;        // elements between consecutive rows of Q and dO
+    const int64_t ks = p.kv_stride_s;     // ... of K, V, dK, dV
 
     for (int r = 0; r < kRowsPerWave; ++r) {
         const int key = (blockIdx.x * kWaves + wave) * kRowsPerWave + r;
@@ -209,33 +213,41 @@ bwd_dkv_generic_kernel(StepArgs p) {
         const int a_first = (p.kind == MASK_FULL) ? 0 : key + p.off;
         if (a_first >= p.c) continue;
         for (int t = lane; t < d; t += 64) {
-            k_lds[wave][t] = ld<T>(K + (int64_t)key * ss + t);
-            v_lds[wave][t] = ld<T>(V + (int64_t)key * ss + t);
+            k_lds[wave][t] = ld<T>(K + (int64_t)key * ks + t);
+            v_lds[wave][t] = ld<T>(V + (int64_t)key * ks + t);
         }
         float acc_k[kMaxD / 64], acc_v[kMaxD / 64];
 #pragma unroll
         for (int i = 0; i < kMaxD / 64; ++i) acc_k[i] = acc_v[i] = 0.f;
         __builtin_amdgcn_wave_barrier();
-        for (int a0 = a_first; a0 < p.c; a0 += 64) {
-            const int a = a0 + lane;
-            float pr = 0.f, ds = 0.f;
-            if (a < p.c) {
-                const float s = p.scale * dot_row<T>(k_lds[wave], Q + (int64_t)a * ss, d);
-                pr = expf(s - L[a]);
-                const float dp = dot_row<T>(v_lds[wave], G + (int64_t)a * ss, d);
-                ds = pr * (dp - D[a]);
-            }
-            const int na = min(64, p.c - a0);
-            for (int kk = 0; kk < na; ++kk) {
-                const float x = __shfl(pr, kk), y = __shfl(ds, kk);
-                const T* grow = G + (int64_t)(a0 + kk) * ss;
-                const T* qrow = Q + (int64_t)(a0 + kk) * ss;
+        for (int member = 0; member < group; ++member) {
+            const int h = kvh * group + member;
+            const int64_t base = b * p.stride_b + h * p.stride_h;
+            const T* Q = (const T*)p.q + base;
+            const T* G = (const T*)p.dout + base;
+            const float* L = p.lse + b * p.stat_stride_b + h * p.stat_stride_h;
+            const float* D = p.delta + b * p.stat_stride_b + h * p.stat_stride_h;
+            for (int a0 = a_first; a0 < p.c; a0 += 64) {
+                const int a = a0 + lane;
+                float pr = 0.f, ds = 0.f;
+                if (a < p.c) {
+                    const float s = p.scale * dot_row<T>(k_lds[wave], Q + (int64_t)a * ss, d);
+                    pr = expf(s - L[a]);
+                    const float dp = dot_row<T>(v_lds[wave], G + (int64_t)a * ss, d);
+                    ds = pr * (dp - D[a]);
+                }
+                const int na = min(64, p.c - a0);
+                for (int kk = 0; kk < na; ++kk) {
+                    const float x = __shfl(pr, kk), y = __shfl(ds, kk);
+                    const T* grow = G + (int64_t)(a0 + kk) * ss;
+                    const T* qrow = Q + (int64_t)(a0 + kk) * ss;
 #pragma unroll
-                for (int i = 0; i < kMaxD / 64; ++i) {
-                    const int t = lane + 64 * i;
-                    if (t < d) {
-                        acc_v[i] = fmaf(x, ld<T>(grow + t), acc_v[i]);
-                        acc_k[i] = fmaf(y, ld<T>(qrow + t), acc_k[i]);
+                    for (int i = 0; i < kMaxD / 64; ++i) {
+                        const int t = lane + 64 * i;
+                        if (t < d) {
+                            acc_v[i] = fmaf(x, ld<T>(grow + t), acc_v[i]);
+                            acc_k[i] = fmaf(y, ld<T>(qrow + t), acc_k[i]);
+                        }
                     }
                 }
             }
@@ -244,36 +256,36 @@ bwd_dkv_generic_kernel(StepArgs p) {
         for (int i = 0; i < kMaxD / 64; ++i) {
             const int t = lane + 64 * i;
             if (t < d) {
-                DV[(int64_t)key * ss + t] += acc_v[i];
-                DK[(int64_t)key * ss + t] += p.scale * acc_k[i];
+                DV[(int64_t)key * ks + t] += acc_v[i];
+                DK[(int64_t)key * ks + t] += p.scale * acc_k[i];
             }
         }
         __builtin_amdgcn_wave_barrier();
     }
 }
 
-dim3 row_grid(const StepArgs& a) {
+dim3 row_grid(const StepArgs& a, int heads) {
     const int rows_per_block = kWaves * kRowsPerWave;
-    return dim3((a.c + rows_per_block - 1) / rows_per_block, a.B * a.H);
+    return dim3((a.c + rows_per_block - 1) / rows_per_block, a.B * heads);
 }
 
 }  // namespace
 
 hipError_t launch_fwd_generic(const StepArgs& a, int dtype, hipStream_t st) {
     if (dtype == SA_F32)
-        hipLaunchKernelGGL(fwd_generic_kernel<float>, row_grid(a), dim3(kWaves * 64), 0, st, a);
+        hipLaunchKernelGGL(fwd_generic_kernel<float>, row_grid(a, a.H), dim3(kWaves * 64), 0, st, a);
     else
-        hipLaunchKernelGGL(fwd_generic_kernel<__hip_bfloat16>, row_grid(a), dim3(kWaves * 64), 0, st, a);
+        hipLaunchKernelGGL(fwd_generic_kernel<__hip_bfloat16>, row_grid(a, a.H), dim3(kWaves * 64), 0, st, a);
     return hipGetLastError();
 }
 
 hipError_t launch_bwd_generic(const StepArgs& a, int dtype, hipStream_t st) {
     if (dtype == SA_F32) {
-        hipLaunchKernelGGL(bwd_dq_generic_kernel<float>, row_grid(a), dim3(kWaves * 64), 0, st, a);
-        hipLaunchKernelGGL(bwd_dkv_generic_kernel<float>, row_grid(a), dim3(kWaves * 64), 0, st, a);
+        hipLaunchKernelGGL(bwd_dq_generic_kernel<float>, row_grid(a, a.H), dim3(kWaves * 64), 0, st, a);
+        hipLaunchKernelGGL(bwd_dkv_generic_kernel<float>, row_grid(a, a.H_kv), dim3(kWaves * 64), 0, st, a);
     } else {
-        hipLaunchKernelGGL(bwd_dq_generic_kernel<__hip_bfloat16>, row_grid(a), dim3(kWaves * 64), 0, st, a);
-        hipLaunchKernelGGL(bwd_dkv_generic_kernel<__hip_bfloat16>, row_grid(a), dim3(kWaves * 64), 0, st, a);
+        hipLaunchKernelGGL(bwd_dq_generic_kernel<__hip_bfloat16>, row_grid(a, a.H), dim3(kWaves * 64), 0, st, a);
+        hipLaunchKernelGGL(bwd_dkv_generic_kernel<__hip_bfloat16>, row_grid(a, a.H_kv), dim3(kWaves * 64), 0, st, a);
     }
     return hipGetLastError();
 }

@@ -26,6 +26,13 @@ struct StepArgs {
     int B, H, c, d;
     int64_t stride_b, stride_h, stat_stride_b, stat_stride_h;
     int64_t stride_s;     // elements between consecutive rows (>= d)
+    // K, V, dK, dV: H_kv heads (H_kv divides H; query head h reads head h / (H / H_kv)) with
+    // strides of their own; equal to H and the strides above for plain multi-head attention
+    int H_kv;
+    int64_t kv_stride_b, kv_stride_h, kv_stride_s;
+    // dK/dV kernels run once per member of a group of H / H_kv query heads: this launch takes
+    // query head kv_head * (H / H_kv) + member
+    int member;
     float scale;
     int kind;             // MaskKind (never MASK_EMPTY at launch)
     int off;              // 0 or 1 when kind == MASK_TRI

@@ -72,6 +72,18 @@ def test_argument_errors_are_reported_before_any_launch():
     assert f(p, p, p, p, p, 0, 0, 4, 0, ctypes.byref(_shape(stride_h=10)), None) == -2
     assert f(p, p, p, p, p, 0, 0, 4, 0, ctypes.byref(_shape(dtype=sa.BF16, stride_h=256 * 64 + 2)),
              None) == -6
+    # fewer key/value heads: H_kv must divide H, and K/V strides obey the same rules as Q's
+    kv = dict(kv_stride_b=256 * 64, kv_stride_h=256 * 64, kv_stride_s=0)
+    assert f(p, p, p, p, p, 0, 0, 4, 0, ctypes.byref(_shape(H=3, stride_b=3 * 256 * 64, H_kv=2, **kv)), None) == -2
+    assert f(p, p, p, p, p, 0, 0, 4, 0, ctypes.byref(_shape(H_kv=-1, **kv)), None) == -2
+    assert f(p, p, p, p, p, 0, 0, 4, 0, ctypes.byref(_shape(H_kv=1, kv_stride_b=0, kv_stride_h=8, kv_stride_s=0)),
+             None) == -2
+    assert f(p, p, p, p, p, 0, 0, 4, 0, ctypes.byref(_shape(H_kv=1, kv_stride_b=0, kv_stride_h=64 * 64,
+                                                           kv_stride_s=32)), None) == -2
+    assert f(p, p, p, p, p, 0, 0, 4, 0, ctypes.byref(_shape(H_kv=1, kv_stride_b=0, kv_stride_h=64 * 66,
+                                                           kv_stride_s=66)), None) == -6
+    # with H_kv = 0 the K/V fields are not looked at
+    assert f(p, p, p, p, p, 0, 1, 4, sa.CONTIGUOUS, ctypes.byref(_shape(H_kv=0, kv_stride_h=-5)), None) == 0
     # an entirely masked contiguous step is a no-op that succeeds without a launch
     assert f(p, p, p, p, p, 0, 1, 4, sa.CONTIGUOUS, ctypes.byref(ok), None) == 0
 
@@ -91,6 +103,8 @@ def test_argument_errors_are_reported_before_any_launch():
     r = L.sa_ring_fwd
     assert r(p, p, p, p, p, 4, 1, ctypes.byref(ok), 4, None, None) == -3
     assert r(p, p, p, p, p, 8, 1, ctypes.byref(ok), -1, None, None) == -2   # strides hold only 4 shards
+    assert r(p, p, p, p, p, 4, 1, ctypes.byref(_shape(H_kv=1, kv_stride_b=0, kv_stride_h=128 * 64)), -1, None,
+             None) == -2                                                    # K/V strides hold only 2 shards
     assert L.sa_state_init(p, null, ctypes.byref(ok), None) == -1
     assert L.sa_finalize(p, odd, ctypes.byref(ok), None) == -6
     assert L.sa_bwd_preprocess(p, p, null, ctypes.byref(ok), None) == -1
