@@ -8,8 +8,9 @@
  *    The caller owns every buffer; the library allocates no device memory.
  *  - Q/K/V/dO/O/dQ/dK/dV are indexed [batch, head, row, 0..d) with d contiguous;
  *    batch, head and row strides are given in elements and are the same for all
- *    of them, so both [B, H, rows, d] (stride_s = d) and [B, rows, H, d]
- *    (stride_h = d, stride_s = H d) memory orders work.  A device's shard of c
+ *    of them (K, V, dK, dV take their own when sa_shape.H_kv is set), so both
+ *    [B, H, rows, d] (stride_s = d) and [B, rows, H, d] (stride_h = d,
+ *    stride_s = H d) memory orders work.  A device's shard of c
  *    rows is a row offset into such a tensor.  LSE and delta are [B, H, rows]
  *    fp32 (rows contiguous) with their own batch/head strides.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
