@@ -57,3 +57,54 @@ def test_random_shapes_forward_and_backward(case):
     assert hp.max_abs_err(back(LSE), Lw) <= (1e-3 if bf16 else 1e-5)
     for g, w in zip(grads, hp.oracle_backward(Q, K, V, dO, sc)):
         assert hp.max_abs_err(back(g), w) <= (2e-2 if bf16 else 2e-5) * max(1.0, float(np.max(np.abs(w))))
+
+
+def _grouped_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        N = int(rng.choice([1, 2, 3, 4]))
+        if i % 2:
+            c, d, dtype = 128 * int(rng.integers(1, 4)), int(rng.choice([128, 100, 64])), torch.bfloat16
+        else:
+            c, d = int(rng.integers(1, 70)), 4 * int(rng.integers(1, 33))
+            dtype = torch.float32 if rng.random() < 0.5 else torch.bfloat16
+        H_kv, group = int(rng.integers(1, 4)), int(rng.integers(1, 5))
+        layout = sa.STRIPED if rng.random() < 0.6 else sa.CONTIGUOUS
+        out.append((int(rng.integers(1, 3)), H_kv * group, H_kv, c, N, d, dtype, layout, bool(rng.random() < 0.5),
+                    int(rng.integers(1, 10 ** 6))))
+    return out
+
+
+@pytest.mark.parametrize("case", _grouped_cases(12, 9431), ids=lambda c: "B%dH%dkv%dc%dN%dd%d" % c[:6])
+def test_random_grouped_head_shapes(case):
+    # fewer key/value heads than query heads, in [B, heads, S, d] or [B, S, heads, d] storage
+    import oracle.striped_attention as orc
+    B, H, H_kv, c, N, d, dtype, layout, seq_major, seed = case
+    S = c * N
+    Q = inputs.gaussian((B, H, S, d), seed, dtype)
+    K = inputs.gaussian((B, H_kv, S, d), seed + 1, dtype)
+    V = inputs.gaussian((B, H_kv, S, d), seed + 2, dtype)
+    dO = inputs.gaussian((B, H, S, d), seed + 3, dtype)
+    dev = [hp.to_device_order(x.cuda(), N, layout) for x in (Q, K, V, dO)]
+    if seq_major:
+        dev = [x.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for x in dev]
+    Qp, Kp, Vp, Gp = dev
+    O = torch.empty_like(Qp, dtype=torch.float32)
+    LSE = torch.empty(B, H, S, dtype=torch.float32, device="cuda")
+    delta = torch.empty_like(LSE)
+    dQ = torch.empty_like(O)
+    dK, dV = (torch.empty_like(Kp, dtype=torch.float32) for _ in range(2))
+    shape = sa.shard_shape(Qp, c, LSE, None, kv=Kp)
+    sa.sa_ring_fwd(Qp, Kp, Vp, O, LSE, N, layout, shape)
+    sa.sa_ring_bwd(Qp, Kp, Vp, Gp, O, LSE, delta, dQ, dK, dV, N, layout, shape)
+    torch.cuda.synchronize()
+    back = lambda t: hp.from_device_order_host(t.cpu().numpy(), N, layout)
+    bf16 = dtype == torch.bfloat16
+    f = [inputs.to_f64(x) for x in (Q, K, V, dO)]
+    sc = 1.0 / np.sqrt(d)
+    Ow, Lw = orc.causal_attention_gqa(f[0], f[1], f[2], sc)
+    assert hp.max_abs_err(back(O), Ow) <= (2e-2 if bf16 else 1e-5)
+    assert hp.max_abs_err(back(LSE), Lw) <= (1e-3 if bf16 else 1e-5)
+    for g, w in zip((dQ, dK, dV), orc.causal_attention_gqa_grad(*f, sc)):
+        assert hp.max_abs_err(back(g), w) <= (2e-2 if bf16 else 2e-5) * max(1.0, float(np.max(np.abs(w))))
