@@ -261,11 +261,22 @@ __device__ inline void mfma_vgpr_acc(f32x16& acc, bf16x8 a, bf16x8 b) {
 // budget).  Q and dO tiles (64 query rows) stream global -> LDS directly into swizzled
 // tiles, two buffers each; LSE * log2(e) and delta of the tile's rows are staged
 // beside them.  Iteration u over 32-query sub-tiles issues, interleaved slice by slice,
-//     S(u+1) = Q(u+1) K^T, dP(u+1) = dO(u+1) V^T   (16 MFMA)
-//     P(u) = exp2(S(u) kappa - LSE), dS(u) = P (dP(u) - delta)   (VALU)
+//     S(u+1) = Q(u+1) K^T, dP(u+1) = dO(u+1) V^T - delta   (16 MFMA; the dP accumulators
+//                              start from -delta, read from LDS, instead of from zero)
+//     P(u) = exp2(S(u) kappa - LSE), dS(u) = P dP(u)   (VALU)
 // and then dV^T += dO(u)^T P(u), dK^T += Q(u)^T dS(u) (16 MFMA, the transposed
 // operands through the transposing LDS read).
-constexpr int KV_STAT_FLOATS = 2 * 2 * DT_ROWS;              // [buffer][lse2 | delta][64]
+constexpr int KV_STAT_FLOATS = 2 * 2 * DT_ROWS;              // [buffer][lse2 | -delta][64]
+
+// -delta of the 32 query rows of a sub-tile as the initial dP^T accumulator: register r holds
+// query row 8 (r/4) + 4h + r%4
+__device__ inline void load_neg_delta(f32x16& dp, const float* neg_delta, int h) {
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const float4 x = *reinterpret_cast<const float4*>(neg_delta + 8 * g + 4 * h);
+        dp[4 * g + 0] = x.x; dp[4 * g + 1] = x.y; dp[4 * g + 2] = x.z; dp[4 * g + 3] = x.w;
+    }
+}
 
 template <bool NEXT, bool MASK>
 __device__ inline void dkdv_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, f32x16& dp_next,
@@ -273,8 +284,9 @@ __device__ inline void dkdv_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, 
                                  const bf16x8 (&vf)[8], float kappa, const uint32_t (&arow)[8],
                                  const uint32_t (&tr0)[4], const uint32_t (&tr1)[4], const char* q_next,
                                  const char* g_next, const char* q_cur, const char* g_cur,
-                                 const float* stat_cur, int h, int mask_lim) {
+                                 const float* stat_cur, const float* stat_next, int h, int mask_lim) {
     bf16x8 qa[8], ga[8], qt[8], gt[8], pb[2], dsb[2];
+    if (NEXT) load_neg_delta(dp_next, stat_next + DT_ROWS, h);
     auto fetch = [&](int i) {
         if (NEXT) {
             qa[i] = dt_read_row(q_next, arow[i]);
@@ -285,11 +297,10 @@ __device__ inline void dkdv_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, 
         gt[i] = dt_read_tr(g_cur + (i / 4) * 16 * 256, tr0[i % 4], tr1[i % 4]);
         qt[i] = dt_read_tr(q_cur + (i / 4) * 16 * 256, tr0[i % 4], tr1[i % 4]);
     };
-    // LSE * log2(e) and delta of this lane's query rows 8 (r/4) + 4h + r%4, two per slice
-    float2 lv[8], dv[8];
+    // LSE * log2(e) of this lane's query rows 8 (r/4) + 4h + r%4, two per slice
+    float2 lv[8];
     auto fetch_stat = [&](int i) {
         lv[i] = *reinterpret_cast<const float2*>(stat_cur + 8 * (i / 2) + 4 * h + 2 * (i % 2));
-        dv[i] = *reinterpret_cast<const float2*>(stat_cur + DT_ROWS + 8 * (i / 2) + 4 * h + 2 * (i % 2));
     };
     constexpr int AHEAD = 2;
 #pragma unroll
@@ -306,21 +317,17 @@ __device__ inline void dkdv_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, 
         }
         if (i >= 5) fetch_t(i - 5);                 // transposed operands 0..2 ahead of their use
         if (NEXT) {
-            if (i == 0) {
-                mfma_vgpr_first(s_next, qa[0], kf[0]);
-                mfma_vgpr_first(dp_next, ga[0], vf[0]);
-            } else {
-                mfma_vgpr_acc(s_next, qa[i], kf[i]);
-                mfma_vgpr_acc(dp_next, ga[i], vf[i]);
-            }
+            if (i == 0) mfma_vgpr_first(s_next, qa[0], kf[0]);
+            else mfma_vgpr_acc(s_next, qa[i], kf[i]);
+            mfma_vgpr_acc(dp_next, ga[i], vf[i]);
         }
 #pragma unroll
         for (int r = 2 * i; r < 2 * i + 2; ++r) {
-            const float lr = (r & 1) ? lv[i].y : lv[i].x, dr = (r & 1) ? dv[i].y : dv[i].x;
+            const float lr = (r & 1) ? lv[i].y : lv[i].x;
             float pr = __builtin_amdgcn_exp2f(fmaf(s_cur[r], kappa, -lr));
             if (MASK && 8 * (r / 4) + (r % 4) < mask_lim) pr = 0.f;
             pb[r / 8][r % 8] = (__bf16)pr;
-            dsb[r / 8][r % 8] = (__bf16)(pr * (dp_cur[r] - dr));
+            dsb[r / 8][r % 8] = (__bf16)(pr * dp_cur[r]);
         }
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -391,10 +398,10 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
     dt_load(Qr, (t_first + 1) * tile_pitch, q_lds1, gl, wave);
     dt_load(Gr, (t_first + 1) * tile_pitch, g_lds1, gl, wave);
     // statistics of query tile t -> stat[(t & 1)][0 | 1][64]: threads 0..63 LSE * log2(e), 64..127
-    // delta.  The fetch is branch-free (wavefronts 2 and 3 re-read what 0 and 1 read and drop
+    // -delta.  The fetch is branch-free (wavefronts 2 and 3 re-read what 0 and 1 read and drop
     // it), so nothing waits for it before the store one trip later.
     const float* stat_src = ((tid & DT_ROWS) ? DEL : LSE) + (tid & (DT_ROWS - 1)) + t_first * DT_ROWS;
-    const float stat_mul = (tid & DT_ROWS) ? 1.f : LOG2E;
+    const float stat_mul = (tid & DT_ROWS) ? -1.f : LOG2E;
     auto stat_fetch = [&]() -> float {          // tiles in order: the pointer walks with them
         const float x = *stat_src;
         stat_src += DT_ROWS;
@@ -423,8 +430,9 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
     {   // prologue: S, dP of the first sub-tile
         const char* q0p = q_lds0;
         const char* g0p = g_lds0;
+        load_neg_delta(dp_a, stat + DT_ROWS, h);          // tile t_first is in buffer 0
         mfma_vgpr_first(s_a, dt_read_row(q0p, arow[0]), kf[0]);
-        mfma_vgpr_first(dp_a, dt_read_row(g0p, arow[0]), vf[0]);
+        mfma_vgpr_acc(dp_a, dt_read_row(g0p, arow[0]), vf[0]);
 #pragma unroll
         for (int ks = 1; ks < 8; ++ks) {
             mfma_vgpr_acc(s_a, dt_read_row(q0p, arow[ks]), kf[ks]);
@@ -443,15 +451,16 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
         char* const q_nxt = PAR ? q_lds0 : q_lds1;
         char* const g_nxt = PAR ? g_lds0 : g_lds1;
         const float* st = stat + PAR * 2 * DT_ROWS;
+        const float* st_nxt = stat + (1 - PAR) * 2 * DT_ROWS;       // statistics of tile t + 1
         dkdv_step<true, MASK>(s_a, dp_a, s_b, dp_b, acck, accv, kf, vf, kappa, arow, tr0, tr1,
-                              q_cur + DT_BYTES / 2, g_cur + DT_BYTES / 2, q_cur, g_cur, st, h,
+                              q_cur + DT_BYTES / 2, g_cur + DT_BYTES / 2, q_cur, g_cur, st, st + 32, h,
                               mask_base - 64 * t);
         if (!last) {
             if (t > t_first) stat_store(t + 1, rstat);     // fetched at the end of trip t-1
             __builtin_amdgcn_s_waitcnt(0);       // tile t+1, requested one iteration ago, has landed
             __syncthreads();
             dkdv_step<true, MASK>(s_b, dp_b, s_a, dp_a, acck, accv, kf, vf, kappa, arow, tr0, tr1, q_nxt,
-                                  g_nxt, q_cur + DT_BYTES / 2, g_cur + DT_BYTES / 2, st + 32, h,
+                                  g_nxt, q_cur + DT_BYTES / 2, g_cur + DT_BYTES / 2, st + 32, st_nxt, h,
                                   mask_base - 64 * t - 32);
             __syncthreads();                     // every wavefront is done with tile t
             if (t + 2 < n_qt) {
@@ -461,7 +470,7 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
             }
         } else {
             dkdv_step<false, MASK>(s_b, dp_b, s_a, dp_a, acck, accv, kf, vf, kappa, arow, tr0, tr1, q_nxt,
-                                   g_nxt, q_cur + DT_BYTES / 2, g_cur + DT_BYTES / 2, st + 32, h,
+                                   g_nxt, q_cur + DT_BYTES / 2, g_cur + DT_BYTES / 2, st + 32, st_nxt, h,
                                    mask_base - 64 * t - 32);
         }
     };
