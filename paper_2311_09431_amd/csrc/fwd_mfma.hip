@@ -26,10 +26,12 @@
 // i.e. one exp2 and about three other VALU instructions per MFMA.
 //
 // Online softmax in base 2 with a lazily updated reference m: kappa = scale *
-// log2(e) is folded into the exponent, p = exp2(s * kappa - m), and m moves
-// only when a row's sub-tile maximum exceeds it by more than 2^RESCALE_LOG2, so
-// the rescaling of l, of the 64 accumulator registers and of the pending
-// probabilities almost never runs.  The running
+// log2(e) is folded into the exponent, p = exp2(s * kappa - m).  The common path
+// never looks for a row maximum: sums of floating-point numbers do not care about
+// a common factor, so m only has to move when a row's partial sum of probabilities
+// exceeds RESCALE_SUM (or the row has no reference yet); then the sub-tile is redone
+// against its row maximum and l and the 64 accumulator registers are rescaled,
+// which almost never runs.  The running
 // state enters as (acc = O, m = LSE * log2(e), l = 1) and leaves as O = acc / l,
 // LSE = (m + log2 l) * ln 2, which is the log-sum-exp merge of the step's
 // partial result with the running one.  Row sums are taken over the fp32
@@ -59,18 +61,22 @@ constexpr int BM = 32 * NW;             // query rows per workgroup
 constexpr int D = TD;                   // columns of a tile: head dimensions below it are zero-padded
 constexpr int TILE_ROWS = 64;           // key rows per LDS tile
 constexpr int TILE_BYTES = TILE_ROWS * D * 2;   // 16 KiB
-constexpr float RESCALE_LOG2 = 8.f;
+constexpr float RESCALE_SUM = 16777216.f;      // 2^24: a row's partial sum of probabilities beyond which its
+                                                // reference is moved up to the row maximum
 
 typedef __attribute__((address_space(3))) char lds_char;
 typedef lds_s16x4_t lds_s16x4;
 
-// One tile (64 rows) of K or V: 16 KiB = 16 wavefront loads of 1 KiB, 4 per wavefront.
-// g[j]: this lane's byte offset into the tile for its j-th load.
+// One tile (64 rows) of K or V: 16 KiB = 16 wavefront loads of 1 KiB (4 rows), 4 per wavefront.
 constexpr int LPW = 16 / NW;             // direct loads per wavefront and tile
-__device__ inline void load_tile_direct(dt_rsrc matrix, int tile_byte_offset, char* lds_tile, const uint32_t (&g)[4],
-                                        int wave) {
+// K: piece j of wavefront w covers tile rows 16 j + 4 w .. + 3.  K's swizzle depends on the
+// row modulo 16, which is then the same for a lane's four pieces: one lane offset g0, the
+// rest (16 j rows) goes into the scalar offset.
+__device__ inline void load_tile_direct(dt_rsrc matrix, int tile_byte_offset, char* lds_tile, uint32_t g0, int wave,
+                                        int pitch) {
 #pragma unroll
-    for (int j = 0; j < LPW; ++j) dt_load_piece(matrix, tile_byte_offset, g[j], lds_tile + (LPW * wave + j) * 1024);
+    for (int j = 0; j < LPW; ++j)
+        dt_load_piece(matrix, tile_byte_offset + j * 16 * pitch, g0, lds_tile + (4 * j + wave) * 1024);
 }
 
 __device__ inline void load_v_tile_direct(dt_rsrc matrix, int tile_byte_offset, char* lds_tile, uint32_t g0, int wave,
@@ -80,6 +86,18 @@ __device__ inline void load_v_tile_direct(dt_rsrc matrix, int tile_byte_offset, 
         dt_load_piece(matrix, tile_byte_offset + j * 4 * pitch, g0, lds_tile + (LPW * wave + j) * 1024);
 }
 
+// LDS address of this lane's K operand for k-step ks: chunk (2 ks + h) ^ (n & 15) of row n.
+// Steps 4..7 differ from steps 0..3 in bit 3 of the chunk index only.  The triangular kernel
+// is two registers short of keeping all eight addresses out of scratch memory in its hot
+// loop, so there (DERIVE) the upper four are made by one XOR each where they are used (the
+// asm keeps the compiler from hoisting them back into registers).
+template <bool DERIVE>
+__device__ inline uint32_t k_step_addr(const uint32_t (&kaddr)[8], int ks) {
+    if (!DERIVE || ks < 4) return kaddr[ks];
+    uint32_t a;
+    asm volatile("v_xor_b32 %0, 0x80, %1" : "=v"(a) : "v"(kaddr[ks - 4]));
+    return a;
+}
 __device__ inline bf16x8 lds_read_b128(const char* lds, uint32_t addr) {
     return *reinterpret_cast<const bf16x8*>(lds + addr);
 }
@@ -95,7 +113,7 @@ __device__ inline bf16x8 lds_read_tr(const char* lds, uint32_t addr) {
 //   PV: oacc += V(u-1)^T p_prev        v_prev = LDS address of the 32 V rows of sub-tile u-1
 // MASK applies the element mask to s_cur: register r (key 8 (r/4) + 4h + r%4 of the
 // sub-tile) is allowed iff 8 (r/4) + r%4 <= mask_lim (mask_lim already holds -4h).
-template <bool QK, bool SM, bool PV, bool MASK>
+template <bool QK, bool SM, bool PV, bool MASK, bool DERIVE>
 __device__ inline void step(f32x16& s_cur, f32x16& s_next, bf16x8 (&p_cur)[2], bf16x8 (&p_prev)[2],
                             f32x16 (&oacc)[4], const bf16x8 (&qf)[8], float& m, float& l, float kappa,
                             const uint32_t (&kaddr)[8], const uint32_t (&vaddr)[4], const char* k_next,
@@ -105,7 +123,7 @@ __device__ inline void step(f32x16& s_cur, f32x16& s_next, bf16x8 (&p_cur)[2], b
     // (16-key group i / 4, 32-column block i % 4).
     bf16x8 ka[8], va[8];
     auto fetch = [&](int i) {
-        if (QK) ka[i] = lds_read_b128(k_next, kaddr[i]);
+        if (QK) ka[i] = lds_read_b128(k_next, k_step_addr<DERIVE>(kaddr, i));
         if (PV) va[i] = lds_read_tr(v_prev + (i / 4) * 16 * 256, vaddr[i % 4]);
     };
     fetch(0);
@@ -116,27 +134,6 @@ __device__ inline void step(f32x16& s_cur, f32x16& s_next, bf16x8 (&p_cur)[2], b
 #pragma unroll
             for (int r = 0; r < 16; ++r)
                 if (8 * (r / 4) + (r % 4) > mask_lim) s_cur[r] = -INFINITY;
-        }
-        float mx = fmaxf(s_cur[0], s_cur[1]);
-#pragma unroll
-        for (int r = 2; r < 16; ++r) mx = fmaxf(mx, s_cur[r]);
-        mx = half_wave_max(mx);
-        const float cand = mx * kappa;
-        if (__builtin_amdgcn_ballot_w64(cand > m + RESCALE_LOG2) != 0) {      // wave-uniform, rare
-            const float m_new = fmaxf(m, cand);
-            const float alpha = __builtin_amdgcn_exp2f(m - ((m_new == -INFINITY) ? 0.f : m_new));
-            m = m_new;
-            l *= alpha;
-#pragma unroll
-            for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[mb][r] *= alpha;
-            if (PV) {   // the pending probabilities were taken against the old reference
-#pragma unroll
-                for (int g = 0; g < 2; ++g)
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) p_prev[g][e] = (__bf16)(alpha * (float)p_prev[g][e]);
-            }
         }
         m_use = (m == -INFINITY) ? 0.f : m;        // row with no key so far
     }
@@ -161,7 +158,37 @@ __device__ inline void step(f32x16& s_cur, f32x16& s_next, bf16x8 (&p_cur)[2], b
         }
     }
     __builtin_amdgcn_sched_barrier(0);
-    if (SM) l += rs0 + rs1;
+    if (SM) {
+        float rs = rs0 + rs1;
+        // The probabilities above were taken against the reference as it stood, without looking
+        // at the scores first.  That is exact as long as nothing overflows (a floating-point
+        // sum does not care about a common factor), so the reference only has to move when a
+        // row's partial sum grows out of hand, or when the row has no reference yet; then the
+        // sub-tile is redone against the row maximum.  Wave-uniform and rare.
+        if (__builtin_amdgcn_ballot_w64(!(rs < RESCALE_SUM) || m == -INFINITY) != 0) {
+            float mx = fmaxf(s_cur[0], s_cur[1]);
+#pragma unroll
+            for (int r = 2; r < 16; ++r) mx = fmaxf(mx, s_cur[r]);
+            mx = half_wave_max(mx);
+            const float m_new = fmaxf(m, mx * kappa);
+            m_use = (m_new == -INFINITY) ? 0.f : m_new;
+            const float alpha = __builtin_amdgcn_exp2f(m - m_use);
+            m = m_new;
+            l *= alpha;
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[mb][r] *= alpha;
+            rs = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float pr = __builtin_amdgcn_exp2f(fmaf(s_cur[r], kappa, -m_use));
+                rs += pr;
+                p_cur[r / 8][r % 8] = (__bf16)pr;
+            }
+        }
+        l += rs;
+    }
 }
 
 template <bool TRI>
@@ -213,7 +240,7 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     // per-lane addresses: K A-operand reads per k-step, V transposing reads per 32-column
     // block (bytes within a 32-row half tile), and the global byte offsets of this lane's
     // direct loads
-    uint32_t kaddr[8], vaddr[4], kg[4], vg0;
+    uint32_t kaddr[8], vaddr[4], kg0, vg0;      // (the triangular kernel uses kaddr[0..3] only)
     {
         const int x = n & 15;
 #pragma unroll
@@ -223,20 +250,16 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
         for (int mb = 0; mb < 4; ++mb)
             vaddr[mb] = (4 * h + j4) * 256 + ((4 * (mb ^ j4) + 2 * nh + ((i & 3) >> 1)) << 4) + (i & 1) * 8;
         const int lr = lane >> 4, pc = lane & 15;      // row within the 4-row group, physical chunk
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int r = 4 * LPW * wave + 4 * j + lr;     // tile row this lane fills with load j
-            kg[j] = r * pitch + ((pc ^ (r & 15)) << 4);
-        }
+        kg0 = (4 * wave + lr) * pitch + ((pc ^ (4 * wave + lr)) << 4);     // row 4 wave + lr of each 16
         // V's swizzle depends on the row within the 4-row group only, so its four pieces
         // differ by exactly four rows: one lane offset, the rest goes into the scalar offset
         vg0 = (4 * LPW * wave + lr) * pitch + ((pc ^ (lr << 2)) << 4);
     }
 
     // first tiles on their way while the running state is loaded
-    load_tile_direct(K, 0, k_lds0, kg, wave);
+    load_tile_direct(K, 0, k_lds0, kg0, wave, pitch);
     load_v_tile_direct(V, 0, v_lds0, vg0, wave, pitch);
-    load_tile_direct(K, tile_pitch, k_lds1, kg, wave);     // n_kt >= 2 always
+    load_tile_direct(K, tile_pitch, k_lds1, kg0, wave, pitch);     // n_kt >= 2 always
 
     bf16x8 qf[8];
     load_b_frags(qf, Q + (int64_t)a * ss, h, d);
@@ -269,7 +292,7 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) s_a[r] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) s_a = mfma(lds_read_b128(k_lds0, kaddr[ks]), qf[ks], s_a);
+        for (int ks = 0; ks < 8; ++ks) s_a = mfma(lds_read_b128(k_lds0, k_step_addr<TRI>(kaddr, ks)), qf[ks], s_a);
     }
 
     // Trip t = iterations u = 2t and 2t+1 with barrier t between them.  Iteration u does
@@ -288,13 +311,13 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
         char* const k_nxt = PAR ? k_lds0 : k_lds1;
         char* const v_cur = PAR ? v_lds1 : v_lds0;
         char* const v_prv = PAR ? v_lds0 : v_lds1;
-        step<true, true, !FIRST, MASK>(s_a, s_b, p_a, p_b, oacc, qf, m, l, kappa, kaddr, vaddr,
+        step<true, true, !FIRST, MASK, TRI>(s_a, s_b, p_a, p_b, oacc, qf, m, l, kappa, kaddr, vaddr,
                                        k_cur + TILE_BYTES / 2, v_prv + TILE_BYTES / 2, mask_base - 64 * t);
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-        if (HOT || t + 2 < n_kt) load_tile_direct(K, (t + 2) * tile_pitch, k_cur, kg, wave);
+        if (HOT || t + 2 < n_kt) load_tile_direct(K, (t + 2) * tile_pitch, k_cur, kg0, wave, pitch);
         if (HOT || t + 1 < n_kt) load_v_tile_direct(V, (t + 1) * tile_pitch, v_prv, vg0, wave, pitch);
-        step<!LAST, true, true, MASK>(s_b, s_a, p_b, p_a, oacc, qf, m, l, kappa, kaddr, vaddr, k_nxt, v_cur,
+        step<!LAST, true, true, MASK, TRI>(s_b, s_a, p_b, p_a, oacc, qf, m, l, kappa, kaddr, vaddr, k_nxt, v_cur,
                                       mask_base - 64 * t - 32);
     };
     using T = std::true_type;
@@ -344,7 +367,7 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     // final iteration u = 2 n_kt: PV(2 n_kt - 1): V tile n_kt - 1, second half; P in p_b
     {
         const char* v_last = (((n_kt - 1) & 1) ? v_lds1 : v_lds0) + TILE_BYTES / 2;
-        step<false, false, true, false>(s_a, s_b, p_a, p_b, oacc, qf, m, l, kappa, kaddr, vaddr, v_last, v_last, 0);
+        step<false, false, true, false, TRI>(s_a, s_b, p_a, p_b, oacc, qf, m, l, kappa, kaddr, vaddr, v_last, v_last, 0);
     }
 
     // epilogue: normalise, store the merged state

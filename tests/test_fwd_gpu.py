@@ -141,6 +141,31 @@ def test_mfma_matches_generic_kernel_on_large_scores():
     _check_ring(1, 1, 512, 128, 2, sa.STRIPED, torch.bfloat16, seed=5, scale=1.0)
 
 
+@pytest.mark.parametrize("layout", [sa.CONTIGUOUS, sa.STRIPED])
+def test_mfma_scores_far_above_the_running_reference(layout):
+    # q.k of magnitude ~ 50-250 nats with scale 1: exp2 of a score against a reference that
+    # lags behind overflows fp32, and every later block may bring a much larger maximum; the
+    # kernel must notice from the row sums, redo the sub-tile against its row maximum and
+    # stay within tolerance (LSE ~ 200: the 1e-3 bound is 40 ulp of fp32 there)
+    B, H, S, d, N = 1, 2, 1024, 128, 4
+    Q, K, V = inputs.qkv(B, H, S, d, 4242, torch.bfloat16)
+    Q, K = (Q * 2).to(torch.bfloat16), (K * 2).to(torch.bfloat16)
+    O, LSE = hp.ring_forward_gpu(Q.cuda(), K.cuda(), V.cuda(), N, layout, 1.0, True)
+    torch.cuda.synchronize()
+    Oh = hp.from_device_order_host(O.cpu().numpy(), N, layout)
+    Lh = hp.from_device_order_host(LSE.cpu().numpy(), N, layout)
+    Ow, Lw = hp.oracle_forward(Q, K, V, 1.0)
+    assert np.isfinite(Oh).all() and np.isfinite(Lh).all()
+    assert float(np.max(Lw)) > 150.0                      # the case is what it claims to be
+    assert hp.max_abs_err(Oh, Ow) <= 2e-2 and hp.max_abs_err(Lh, Lw) <= 1e-3
+    # all-zero queries: every score equals the reference-free value 0, uniform attention
+    O2, LSE2 = hp.ring_forward_gpu((Q * 0).cuda(), K.cuda(), V.cuda(), N, layout, 1.0, True)
+    torch.cuda.synchronize()
+    Ow2, Lw2 = hp.oracle_forward(Q * 0, K, V, 1.0)
+    assert hp.max_abs_err(hp.from_device_order_host(O2.cpu().numpy(), N, layout), Ow2) <= 2e-2
+    assert hp.max_abs_err(hp.from_device_order_host(LSE2.cpu().numpy(), N, layout), Lw2) <= 1e-3
+
+
 def test_mfma_forward_is_deterministic_and_honours_the_stream():
     # no atomics anywhere: two runs give the same bits; and the work goes to the caller's stream
     B, H, S, d, N = 1, 2, 1024, 128, 4
