@@ -98,5 +98,7 @@ int main() {
     run<3, 1, 3, 2>(out); run<3, 1, 3, 2, false, 1>(out, g);                    // dQ-like
     run<3, 1, 0, 1>(out); run<3, 1, 3, 1>(out); run<3, 1, 4, 1>(out); run<3, 1, 4, 1, false, 1>(out, g);   // dK/dV-like
     run<4, 1, 1, 1>(out); run<4, 1, 2, 1>(out);          // 64 queries per wavefront, one wavefront per SIMD
+    run<2, 1, 3, 2, false, 1>(out, g);                    // brackets the dQ kernel's count from above (2.4 + 0.67 exp)
+    run<2, 1, 4, 1, false, 1>(out, g);                    // brackets the dK/dV kernel's count from above (1.45 + 0.6 exp)
     return 0;
 }
