@@ -20,6 +20,11 @@ pytestmark = pytest.mark.gpu
     (2, 512, 64, 4, torch.float32),      # fp32 rows, d = 64
     (1, 12, 5, 1, torch.uint8),          # N = 1: identity
     (2, 96, 128, 96, torch.bfloat16),    # c = 1
+    (3, 1000, 128, 5, torch.bfloat16),   # 256-byte rows, 1000 rows of 5 devices
+    (2, 84, 1024, 7, torch.float32),     # 4096-byte rows
+    (2, 520, 4, 8, torch.float32),       # 16-byte rows: a single chunk
+    (2, 60, 100, 4, torch.bfloat16),     # 200-byte rows (d = 100): 8-byte chunks
+    (2, 64, 96, 4, torch.bfloat16),      # 192-byte rows: 12 chunks of 16 bytes
 ])
 def test_permute_bit_exact(outer, S, inner, N, dtype):
     g = torch.Generator().manual_seed(S + inner)
