@@ -52,7 +52,7 @@ typedef struct {
     int32_t c;             /* rows per device (block size) */
     int32_t d;             /* head dimension: any multiple of 4 up to 256 (Table 1's
                               models have 128 and 100);
-                              bf16 with d <= 128 and c % 128 == 0 takes the MFMA kernels
+                              bf16 with d <= 128 and c >= 128 takes the MFMA kernels
                               (d < 128 zero-padded to 128 columns) */
     int64_t stride_b;      /* elements between batches in Q/K/V/dO/O/dQ/dK/dV */
     int64_t stride_h;      /* elements between heads in the same tensors */

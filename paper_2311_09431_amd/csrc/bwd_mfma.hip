@@ -94,7 +94,10 @@ __device__ inline void dq_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, f3
     }
 }
 
-template <bool TRI>
+// RAGGED (c not a multiple of 128), as in the forward kernel: loads of rows beyond the shard
+// are clamped, their results are not stored, keys beyond it come in as zero rows and are
+// removed by the element mask (full blocks: mask limit c - 1); implies the triangular path.
+template <bool TRI, bool RAGGED = false>
 __global__ void __launch_bounds__(256, 2)
 bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
     // one LDS object per tile buffer
@@ -123,16 +126,20 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
     const __bf16* G = (const __bf16*)p.dout + base;
     float* DQ = p.dq + base;
 
-    const int q0 = qt * BM, a = q0 + 32 * wave + n;
+    const int q0 = qt * BM, a_own = q0 + 32 * wave + n;
+    const bool row_ok = !RAGGED || a_own < p.c;
+    const int a = RAGGED ? min(a_own, p.c - 1) : a_own;      // the row this lane loads
+    const bool full_block = RAGGED && p.kind == MASK_FULL;   // a full block on the masked code path
     // all four wavefronts walk the 2 n_kt sub-tiles of the workgroup (at most three are
     // entirely masked for a wavefront); the element mask runs on the last four only
-    const int n_kt_fine = TRI ? (q0 + BM) / DT_ROWS : p.c / DT_ROWS;
+    const int n_kt_fine = TRI ? (full_block ? 2 * n_tiles : (q0 + BM) / DT_ROWS) : p.c / DT_ROWS;
     int n_kt = n_kt_fine;
     if (TRI && p.skip_bq > 0) {       // emulated coarse skipping, as in the forward kernel
         const int q_hi = (q0 / p.skip_bq + 1) * p.skip_bq - 1;
         n_kt = min(p.c, ((q_hi - p.off) / p.skip_bk + 1) * p.skip_bk) / DT_ROWS;
     }
-    const int mask_base = a - p.off - 4 * h;     // sub-tile v: allowed iff 8 (r/4) + r%4 <= mask_base - 32 v
+    // sub-tile v: allowed iff 8 (r/4) + r%4 <= mask_base - 32 v
+    const int mask_base = (full_block ? p.c - 1 : a_own - p.off) - 4 * h;
 
     uint32_t arow[8], tr0[4], tr1[4], gl[4];
     dt_row_addrs(arow, n, h);
@@ -233,7 +240,7 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             const int col = 32 * mb + 8 * g + 4 * h;
-            if (col >= d) continue;                       // padding columns
+            if (col >= d || !row_ok) continue;            // padding columns, rows beyond the shard
             float4* dst = reinterpret_cast<float4*>(DQ + (int64_t)a * ss + col);
             float4 x = *dst;
             x.x = fmaf(p.scale, acc[mb][4 * g + 0], x.x); x.y = fmaf(p.scale, acc[mb][4 * g + 1], x.y);
@@ -340,7 +347,10 @@ __device__ inline void dkdv_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, 
     }
 }
 
-template <bool TRI>
+// RAGGED (c not a multiple of 128): key rows beyond the shard are loaded from its last row and
+// not stored; query rows beyond it come in as zero rows of Q and dO with LSE = +inf, so their
+// P and dS are exactly zero.
+template <bool TRI, bool RAGGED = false>
 __global__ void __launch_bounds__(256, 1)
 bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
     // one LDS object per tile buffer
@@ -374,8 +384,10 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
     float* DK = p.dk + kv_base;
     float* DV = p.dv + kv_base;
 
-    const int k0 = ktile * BM, key = k0 + 32 * wave + n;
-    const int n_qt = p.c / DT_ROWS;
+    const int k0 = ktile * BM, key_own = k0 + 32 * wave + n;
+    const bool key_ok = !RAGGED || key_own < p.c;
+    const int key = RAGGED ? min(key_own, p.c - 1) : key_own;     // the row this lane loads
+    const int n_qt = RAGGED ? 2 * n_tiles : p.c / DT_ROWS;
     // query tiles holding at least one allowed pair (query a >= key + off): from tile k0 / 64
     // on; only its first four 32-query sub-tiles can cross the diagonal for some wavefront
     const int t_first_fine = TRI ? k0 / DT_ROWS : 0;
@@ -385,7 +397,7 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
         t_first = ((k0 / p.skip_bk * p.skip_bk + p.off) / p.skip_bq) * p.skip_bq / DT_ROWS;
     // sub-tile u: register r (query 32 u + 8 (r/4) + 4h + r%4) is allowed iff
     // 8 (r/4) + r%4 >= mask_base - 32 u
-    const int mask_base = key + p.off - 4 * h;
+    const int mask_base = key_own + p.off - 4 * h;
 
     uint32_t arow[8], tr0[4], tr1[4], gl[4];
     dt_row_addrs(arow, n, h);
@@ -402,8 +414,16 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
     // it), so nothing waits for it before the store one trip later.
     const float* stat_src = ((tid & DT_ROWS) ? DEL : LSE) + (tid & (DT_ROWS - 1)) + t_first * DT_ROWS;
     const float stat_mul = (tid & DT_ROWS) ? -1.f : LOG2E;
+    int stat_row = (tid & (DT_ROWS - 1)) + t_first * DT_ROWS;      // RAGGED only
     auto stat_fetch = [&]() -> float {          // tiles in order: the pointer walks with them
-        const float x = *stat_src;
+        float x;
+        if (RAGGED) {       // rows beyond the shard: LSE = +inf, delta = 0 (still branch-free)
+            x = stat_src[min(stat_row, p.c - 1) - stat_row];
+            if (stat_row >= p.c) x = (tid & DT_ROWS) ? 0.f : INFINITY;
+            stat_row += DT_ROWS;
+        } else {
+            x = *stat_src;
+        }
         stat_src += DT_ROWS;
         return x;
     };
@@ -504,7 +524,7 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             const int col = 32 * mb + 8 * g + 4 * h;
-            if (col >= d) continue;                       // padding columns
+            if (col >= d || !key_ok) continue;            // padding columns, keys beyond the shard
             const int64_t o = (int64_t)key * ss + col;
             float4 x = *reinterpret_cast<float4*>(DV + o);
             x.x += accv[mb][4 * g + 0]; x.y += accv[mb][4 * g + 1];
@@ -521,27 +541,36 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
 
 bool bwd_mfma_supported(const StepArgs& a, int dtype) {
     // the tile loads address a shard through a buffer descriptor with 32-bit byte offsets:
-    // its last row must end below 2^31 bytes from its first
+    // the last row of its last (possibly partial) tile pair must end below 2^31 bytes from
+    // its first
     const int64_t widest = a.stride_s > a.kv_stride_s ? a.stride_s : a.kv_stride_s;
-    return dtype == SA_BF16 && a.d <= D && a.d % 4 == 0 && a.c % BM == 0 &&
-           (int64_t)(a.c - 1) * 2 * widest + 2 * a.d < (int64_t(1) << 31);
+    const int64_t rows = (int64_t)(a.c + BM - 1) / BM * BM;
+    return dtype == SA_BF16 && a.d <= D && a.d % 4 == 0 && a.c >= BM &&
+           rows * 2 * widest + 2 * a.d < (int64_t(1) << 31);
 }
 
 hipError_t launch_bwd_mfma(const StepArgs& a, hipStream_t st) {
-    const int n_tiles = a.c / BM;
-    if (a.kind == MASK_TRI)
-        hipLaunchKernelGGL(bwd_dq_mfma_kernel<true>, dim3(n_tiles * a.B * a.H), dim3(256), 0, st, a, n_tiles);
+    const int n_tiles = (a.c + BM - 1) / BM;
+    const bool ragged = a.c % BM != 0;
+    const dim3 grid_q(n_tiles * a.B * a.H), grid_kv(n_tiles * a.B * a.H_kv), block(256);
+    if (ragged)
+        hipLaunchKernelGGL((bwd_dq_mfma_kernel<true, true>), grid_q, block, 0, st, a, n_tiles);
+    else if (a.kind == MASK_TRI)
+        hipLaunchKernelGGL((bwd_dq_mfma_kernel<true>), grid_q, block, 0, st, a, n_tiles);
     else
-        hipLaunchKernelGGL(bwd_dq_mfma_kernel<false>, dim3(n_tiles * a.B * a.H), dim3(256), 0, st, a, n_tiles);
+        hipLaunchKernelGGL((bwd_dq_mfma_kernel<false>), grid_q, block, 0, st, a, n_tiles);
     hipError_t e = hipGetLastError();
     // dK, dV: the members of a group of query heads one after the other, each adding to the
     // shared head's accumulators in stream order (deterministic)
     StepArgs m = a;
     for (m.member = 0; m.member < a.H / a.H_kv && e == hipSuccess; ++m.member) {
-        if (a.kind == MASK_TRI)
-            hipLaunchKernelGGL(bwd_dkdv_mfma_kernel<true>, dim3(n_tiles * a.B * a.H_kv), dim3(256), 0, st, m, n_tiles);
-        else
-            hipLaunchKernelGGL(bwd_dkdv_mfma_kernel<false>, dim3(n_tiles * a.B * a.H_kv), dim3(256), 0, st, m, n_tiles);
+        if (a.kind == MASK_TRI) {
+            if (ragged) hipLaunchKernelGGL((bwd_dkdv_mfma_kernel<true, true>), grid_kv, block, 0, st, m, n_tiles);
+            else hipLaunchKernelGGL((bwd_dkdv_mfma_kernel<true>), grid_kv, block, 0, st, m, n_tiles);
+        } else {
+            if (ragged) hipLaunchKernelGGL((bwd_dkdv_mfma_kernel<false, true>), grid_kv, block, 0, st, m, n_tiles);
+            else hipLaunchKernelGGL((bwd_dkdv_mfma_kernel<false>), grid_kv, block, 0, st, m, n_tiles);
+        }
         e = hipGetLastError();
     }
     return e;

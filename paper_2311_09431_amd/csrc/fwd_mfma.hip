@@ -191,7 +191,12 @@ __device__ inline void step(f32x16& s_cur, f32x16& s_next, bf16x8 (&p_cur)[2], b
     }
 }
 
-template <bool TRI>
+// RAGGED: c is not a multiple of 128.  The last query tile then holds rows beyond the shard
+// (their loads are clamped to the last row, their results are not stored) and the last key
+// tiles hold keys beyond it (the tile loads return zeros there, and the element mask of the
+// triangular code path removes them: for a full block the mask limit is the last key, c - 1,
+// instead of the query's own position).  RAGGED implies the triangular code path.
+template <bool TRI, bool RAGGED = false>
 __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1)
 fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     // one LDS object per tile buffer
@@ -220,12 +225,15 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     float* L = p.lse + b * p.stat_stride_b + hd * p.stat_stride_h;
 
     const int q0 = qt * BM;
-    const int a = q0 + 32 * wave + n;         // this lane's query row
+    const int a_own = q0 + 32 * wave + n;     // this lane's query row
+    const bool row_ok = !RAGGED || a_own < p.c;
+    const int a = RAGGED ? min(a_own, p.c - 1) : a_own;      // the row it loads
+    const bool full_block = RAGGED && p.kind == MASK_FULL;   // a full block on the masked code path
     // 64-key tiles holding at least one allowed pair for the workgroup.  Triangular: keys
     // b <= a - off, i.e. tiles 0 .. (q0 + 127) / 64.  All four wavefronts walk all 2 n_kt
     // sub-tiles (at most NW - 1 of them are entirely masked for a wavefront); the element
     // mask is applied on the last NW sub-tiles only.
-    const int n_kt_fine = TRI ? (q0 + BM) / TILE_ROWS : p.c / TILE_ROWS;
+    const int n_kt_fine = TRI ? (full_block ? 2 * n_qtiles : (q0 + BM) / TILE_ROWS) : p.c / TILE_ROWS;
     int n_kt = n_kt_fine;
     if (TRI && p.skip_bq > 0) {
         // emulated coarse skipping: up to the last skip_bk-wide key tile that shares an allowed
@@ -235,7 +243,7 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     }
     // sub-tile v: register r (key 32 v + 8 (r/4) + 4h + r%4) is allowed iff
     // 8 (r/4) + r%4 <= mask_base - 32 v
-    const int mask_base = a - p.off - 4 * h;
+    const int mask_base = (full_block ? p.c - 1 : a_own - p.off) - 4 * h;
 
     // per-lane addresses: K A-operand reads per k-step, V transposing reads per 32-column
     // block (bytes within a 32-row half tile), and the global byte offsets of this lane's
@@ -381,26 +389,31 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
             x.x = oacc[mb][4 * g + 0] * inv; x.y = oacc[mb][4 * g + 1] * inv;
             x.z = oacc[mb][4 * g + 2] * inv; x.w = oacc[mb][4 * g + 3] * inv;
             const int col = 32 * mb + 8 * g + 4 * h;
-            if (col < d) *reinterpret_cast<float4*>(O + (int64_t)a * ss + col) = x;
+            if (col < d && row_ok) *reinterpret_cast<float4*>(O + (int64_t)a * ss + col) = x;
         }
-    if (h == 0) L[a] = (m + __builtin_amdgcn_logf(l_tot)) * LN2;
+    if (h == 0 && row_ok) L[a] = (m + __builtin_amdgcn_logf(l_tot)) * LN2;
 }
 
 }  // namespace
 
 bool fwd_mfma_supported(const StepArgs& a, int dtype) {
     // the tile loads address a shard through a buffer descriptor with 32-bit byte offsets:
-    // its last row must end below 2^31 bytes from its first
-    return dtype == SA_BF16 && a.d <= D && a.d % 4 == 0 && a.c % BM == 0 &&
-           (int64_t)(a.c - 1) * 2 * a.kv_stride_s + 2 * a.d < (int64_t(1) << 31);
+    // the last row of its last (possibly partial) tile pair must end below 2^31 bytes from
+    // its first
+    const int64_t rows = (int64_t)(a.c + BM - 1) / BM * BM;
+    return dtype == SA_BF16 && a.d <= D && a.d % 4 == 0 && a.c >= BM &&
+           rows * 2 * a.kv_stride_s + 2 * a.d < (int64_t(1) << 31);
 }
 
 hipError_t launch_fwd_mfma(const StepArgs& a, hipStream_t st) {
-    const int n_qtiles = a.c / BM;
-    if (a.kind == MASK_TRI)
-        hipLaunchKernelGGL(fwd_mfma_kernel<true>, dim3(n_qtiles * a.B * a.H), dim3(64 * NW), 0, st, a, n_qtiles);
+    const int n_qtiles = (a.c + BM - 1) / BM;
+    const dim3 grid(n_qtiles * a.B * a.H), block(64 * NW);
+    if (a.c % BM)
+        hipLaunchKernelGGL((fwd_mfma_kernel<true, true>), grid, block, 0, st, a, n_qtiles);
+    else if (a.kind == MASK_TRI)
+        hipLaunchKernelGGL((fwd_mfma_kernel<true>), grid, block, 0, st, a, n_qtiles);
     else
-        hipLaunchKernelGGL(fwd_mfma_kernel<false>, dim3(n_qtiles * a.B * a.H), dim3(64 * NW), 0, st, a, n_qtiles);
+        hipLaunchKernelGGL((fwd_mfma_kernel<false>), grid, block, 0, st, a, n_qtiles);
     return hipGetLastError();
 }
 

@@ -1,7 +1,7 @@
 """A seeded sweep over shapes the hand-picked cases may miss: random batch, heads, block size,
 device count, head dimension, storage type, softmax scale and layout, forward and backward,
 each against the fp64 oracle with the usual tolerances.  Half of the bf16 cases are built to
-take the matrix-core kernels (c a multiple of 128, d <= 128), the rest the generic ones."""
+take the matrix-core kernels (here c a multiple of 128, d <= 128), the rest the generic ones."""
 import numpy as np
 import pytest
 import torch
