@@ -108,3 +108,36 @@ def test_random_grouped_head_shapes(case):
     assert hp.max_abs_err(back(LSE), Lw) <= (1e-3 if bf16 else 1e-5)
     for g, w in zip((dQ, dK, dV), orc.causal_attention_gqa_grad(*f, sc)):
         assert hp.max_abs_err(back(g), w) <= (2e-2 if bf16 else 2e-5) * max(1.0, float(np.max(np.abs(w))))
+
+
+def _mixed_cases(n, seed):
+    """Everything at once: block sizes on, off and below the 128-row tiles, grouped heads, both
+    memory orders (shard pointers kept 16-byte aligned, as the entry points require)."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        N = int(rng.choice([1, 2, 3, 4, 6]))
+        kind = i % 3
+        if kind == 0:
+            c, d, dtype = 128 * int(rng.integers(1, 5)), int(rng.choice([128, 100, 64, 4, 120])), torch.bfloat16
+        elif kind == 1:
+            c, d, dtype = int(rng.integers(128, 600)), int(rng.choice([128, 100, 64, 32])), torch.bfloat16
+        else:
+            c, d = int(rng.integers(1, 128)), 4 * int(rng.integers(1, 65))
+            dtype = torch.float32 if rng.random() < 0.5 else torch.bfloat16
+        if c * N > 2200:
+            N = max(1, 2200 // c)
+        H_kv, group = int(rng.integers(1, 4)), int(rng.choice([1, 1, 2, 4]))
+        seq_major = bool(rng.random() < 0.4)
+        es = 2 if dtype == torch.bfloat16 else 4
+        while (c * d * es) % 16 or (seq_major and (c * H_kv * d * es) % 16):
+            c += 1
+        layout = sa.STRIPED if rng.random() < 0.6 else sa.CONTIGUOUS
+        out.append((int(rng.integers(1, 3)), H_kv * group, H_kv, c, N, d, dtype, layout, seq_major,
+                    int(rng.integers(1, 10 ** 6))))
+    return out
+
+
+@pytest.mark.parametrize("case", _mixed_cases(18, 23110), ids=lambda c: "B%dH%dkv%dc%dN%dd%d" % c[:6])
+def test_random_mixed_shapes(case):
+    test_random_grouped_head_shapes(case)
