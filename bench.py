@@ -10,7 +10,8 @@ inputs resident in HBM.  The contiguous (Ring Attention) layout is timed beside
 it for the worst-device step latencies the paper's argument is about (Sec. 1:
 a round lasts as long as its slowest device).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3|cfg2|cfg4|cfg5|tiny]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3|cfg2|cfg4|cfg5|3b|tiny]
+                    [--bwd 0|1] [--cold] [--graph] [--skip-granularity BQxBK] [--kv-heads H_KV]
 
 Prints one JSON line.
 """
@@ -234,8 +235,8 @@ def traffic_fields(workload, name):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
-    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg3", choices=sorted(WORKLOADS))
     ap.add_argument("--bwd", type=int, default=1, help="0: forward ring only (default: forward + backward)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -248,6 +249,8 @@ def main():
     ap.add_argument("--kv-heads", type=int, default=0, metavar="H_KV",
                     help="K and V with H_KV heads shared by groups of query heads (an extension; "
                          "default: as many as query heads, the paper's models)")
+    ap.add_argument("--graph", action="store_true",
+                    help="also record one pass into a HIP graph and time its replays (no per-step events)")
     args = ap.parse_args()
     skip = tuple(int(x) for x in args.skip_granularity.lower().split("x")) if args.skip_granularity else (0, 0)
     if len(skip) != 2:
@@ -371,6 +374,23 @@ def main():
             cold["contiguous"]["ring_sum_ms"] / max(1e-9, cold["striped"]["ring_sum_ms"]), 3)
         cold["note"] = "forward steps, L2 and memory-side cache flushed before each step"
         result["cold_cache"] = cold
+    if args.graph:
+        # the same pass without per-step events, recorded once and replayed: what is left when
+        # the host side (launches, event records) is taken out
+        graph = torch.cuda.CUDAGraph()
+        run.one_pass(sa.STRIPED, False)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph):
+            run.one_pass(sa.STRIPED, False)
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        g_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        result["graph_replay"] = {"ms_per_step": round(g_ms, 4), "value": round(flops / (g_ms * 1e9), 2),
+                                  "unit": "TFLOP/s"}
     result["hbm_bound_kernels"] = hbm_bound_kernels(run)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline()
