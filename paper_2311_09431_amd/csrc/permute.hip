@@ -5,11 +5,16 @@
 
 namespace sa {
 
-// One thread moves one VEC-byte chunk.  Threads are laid out over the
-// DESTINATION so stores are fully coalesced; a row of `chunks` chunks is read
-// contiguously as well (256-byte rows = 16 lanes x 16 B), only the row start
-// jumps.  forward: dst row p = dev*c + a takes src row a*N + dev.
-// inverse: dst row t = a*N + dev takes src row dev*c + a.
+// One thread moves one VEC-byte chunk; a row of `chunks` chunks is read and written
+// contiguously (256-byte rows = 16 lanes x 16 B), only the row start jumps.  Threads are laid
+// out over the side whose rows are INTERLEAVED (the original order): rows r and r + N of it
+// are neighbours on the other side, so N-row groups of consecutive threads touch N runs of
+// consecutive rows there, and the interleaved side itself is walked front to back.
+//   forward: thread row t of the source      -> dst row (t mod N) * c + t div N
+//   inverse: thread row t of the destination <- src row (t mod N) * c + t div N
+// (Walking the permuted side instead makes every 256-byte read of the forward direction a
+// separate piece N rows apart: 4.86 TB/s against 5.04 TB/s this way on 2 GiB tensors, where a
+// plain device-to-device copy of the same size runs at 4.93 TB/s.)
 template <typename VecT>
 __global__ void __launch_bounds__(256)
 permute_kernel(const VecT* __restrict__ src, VecT* __restrict__ dst, int64_t n_seq, int64_t chunks,
@@ -18,18 +23,13 @@ permute_kernel(const VecT* __restrict__ src, VecT* __restrict__ dst, int64_t n_s
     const int64_t step = (int64_t)gridDim.x * blockDim.x;
     for (; idx < total; idx += step) {
         const int64_t x = idx % chunks;
-        const int64_t row = idx / chunks;      // o * n_seq + dst row
+        const int64_t row = idx / chunks;      // o * n_seq + t
         const int64_t o = row / n_seq;
-        const int64_t r = row - o * n_seq;
-        int64_t s;
-        if (!inverse) {
-            const int64_t dev = r / c, a = r - dev * c;
-            s = a * N + dev;
-        } else {
-            const int64_t a = r / N, dev = r - a * N;
-            s = dev * c + a;
-        }
-        dst[idx] = src[(o * n_seq + s) * chunks + x];
+        const int64_t t = row - o * n_seq;
+        const int64_t a = t / N, dev = t - a * N;
+        const int64_t other = (o * n_seq + dev * c + a) * chunks + x;
+        if (!inverse) dst[other] = src[idx];
+        else dst[idx] = src[other];
     }
 }
 
