@@ -87,13 +87,12 @@ __device__ inline void load_v_tile_direct(dt_rsrc matrix, int tile_byte_offset, 
 }
 
 // LDS address of this lane's K operand for k-step ks: chunk (2 ks + h) ^ (n & 15) of row n.
-// Steps 4..7 differ from steps 0..3 in bit 3 of the chunk index only.  The triangular kernel
-// is two registers short of keeping all eight addresses out of scratch memory in its hot
-// loop, so there (DERIVE) the upper four are made by one XOR each where they are used (the
-// asm keeps the compiler from hoisting them back into registers).
-template <bool DERIVE>
-__device__ inline uint32_t k_step_addr(const uint32_t (&kaddr)[8], int ks) {
-    if (!DERIVE || ks < 4) return kaddr[ks];
+// Steps 4..7 differ from steps 0..3 in bit 3 of the chunk index only.  The kernel is two
+// registers short of keeping all eight addresses out of scratch memory in its hot loop, so
+// four are kept and the other four are made by one XOR each where they are used (the asm
+// keeps the compiler from hoisting them back into registers).
+__device__ inline uint32_t k_step_addr(const uint32_t (&kaddr)[4], int ks) {
+    if (ks < 4) return kaddr[ks];
     uint32_t a;
     asm volatile("v_xor_b32 %0, 0x80, %1" : "=v"(a) : "v"(kaddr[ks - 4]));
     return a;
@@ -113,17 +112,17 @@ __device__ inline bf16x8 lds_read_tr(const char* lds, uint32_t addr) {
 //   PV: oacc += V(u-1)^T p_prev        v_prev = LDS address of the 32 V rows of sub-tile u-1
 // MASK applies the element mask to s_cur: register r (key 8 (r/4) + 4h + r%4 of the
 // sub-tile) is allowed iff 8 (r/4) + r%4 <= mask_lim (mask_lim already holds -4h).
-template <bool QK, bool SM, bool PV, bool MASK, bool DERIVE>
+template <bool QK, bool SM, bool PV, bool MASK>
 __device__ inline void step(f32x16& s_cur, f32x16& s_next, bf16x8 (&p_cur)[2], bf16x8 (&p_prev)[2],
                             f32x16 (&oacc)[4], const bf16x8 (&qf)[8], float& m, float& l, float kappa,
-                            const uint32_t (&kaddr)[8], const uint32_t (&vaddr)[4], const char* k_next,
+                            const uint32_t (&kaddr)[4], const uint32_t (&vaddr)[4], const char* k_next,
                             const char* v_prev, int mask_lim) {
     // Operands of slice i are requested from LDS two slices ahead, so only a few of
     // them are live at a time; slice i holds QK MFMA i (k-step i) and PV MFMA i
     // (16-key group i / 4, 32-column block i % 4).
     bf16x8 ka[8], va[8];
     auto fetch = [&](int i) {
-        if (QK) ka[i] = lds_read_b128(k_next, k_step_addr<DERIVE>(kaddr, i));
+        if (QK) ka[i] = lds_read_b128(k_next, k_step_addr(kaddr, i));
         if (PV) va[i] = lds_read_tr(v_prev + (i / 4) * 16 * 256, vaddr[i % 4]);
     };
     fetch(0);
@@ -191,12 +190,15 @@ __device__ inline void step(f32x16& s_cur, f32x16& s_next, bf16x8 (&p_cur)[2], b
     }
 }
 
-// RAGGED: c is not a multiple of 128.  The last query tile then holds rows beyond the shard
-// (their loads are clamped to the last row, their results are not stored) and the last key
-// tiles hold keys beyond it (the tile loads return zeros there, and the element mask of the
-// triangular code path removes them: for a full block the mask limit is the last key, c - 1,
-// instead of the query's own position).  RAGGED implies the triangular code path.
-template <bool TRI, bool RAGGED = false>
+// One code path serves every step: a block is walked up to the last key tile that holds an
+// allowed pair, and the last BM / 64 tiles of the walk carry the element mask.  For a
+// triangular block the mask limit is the query's own position; for a full block (contiguous
+// layout, q_dev > kv_dev) it is the last key, c - 1, which for a multiple of 128 masks
+// nothing.  RAGGED: c is not a multiple of 128.  The last query tile then holds rows beyond
+// the shard (their loads are clamped to the last row, their results are not stored) and the
+// last key tiles hold keys beyond it (the tile loads return zeros there and the mask removes
+// them).
+template <bool RAGGED>
 __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1)
 fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     // one LDS object per tile buffer
@@ -209,7 +211,7 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform, kept scalar
     int rank, bh;
     decode_block<true>((int)blockIdx.x, n_qtiles, p.B * p.H, rank, bh);
-    const int qt = TRI ? n_qtiles - 1 - rank : rank;      // triangular steps: heaviest query tiles first
+    const int qt = n_qtiles - 1 - rank;      // triangular steps: heaviest query tiles first
     const int b = bh / p.H, hd = bh - b * p.H;
     const int64_t base = b * p.stride_b + hd * p.stride_h;
     // key/value head of this query head's group (the same head when H_kv == H)
@@ -228,14 +230,14 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     const int a_own = q0 + 32 * wave + n;     // this lane's query row
     const bool row_ok = !RAGGED || a_own < p.c;
     const int a = RAGGED ? min(a_own, p.c - 1) : a_own;      // the row it loads
-    const bool full_block = RAGGED && p.kind == MASK_FULL;   // a full block on the masked code path
+    const bool full_block = p.kind == MASK_FULL;     // every key allowed: the mask limit is the last key
     // 64-key tiles holding at least one allowed pair for the workgroup.  Triangular: keys
     // b <= a - off, i.e. tiles 0 .. (q0 + 127) / 64.  All four wavefronts walk all 2 n_kt
     // sub-tiles (at most NW - 1 of them are entirely masked for a wavefront); the element
     // mask is applied on the last NW sub-tiles only.
-    const int n_kt_fine = TRI ? (full_block ? 2 * n_qtiles : (q0 + BM) / TILE_ROWS) : p.c / TILE_ROWS;
+    const int n_kt_fine = full_block ? 2 * n_qtiles : (q0 + BM) / TILE_ROWS;
     int n_kt = n_kt_fine;
-    if (TRI && p.skip_bq > 0) {
+    if (!full_block && p.skip_bq > 0) {
         // emulated coarse skipping: up to the last skip_bk-wide key tile that shares an allowed
         // pair with the skip_bq-tall tile these queries belong to
         const int q_hi = (q0 / p.skip_bq + 1) * p.skip_bq - 1;
@@ -248,11 +250,11 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     // per-lane addresses: K A-operand reads per k-step, V transposing reads per 32-column
     // block (bytes within a 32-row half tile), and the global byte offsets of this lane's
     // direct loads
-    uint32_t kaddr[8], vaddr[4], kg0, vg0;      // (the triangular kernel uses kaddr[0..3] only)
+    uint32_t kaddr[4], vaddr[4], kg0, vg0;
     {
         const int x = n & 15;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) kaddr[ks] = n * 256 + (((2 * ks + h) ^ x) << 4);
+        for (int ks = 0; ks < 4; ++ks) kaddr[ks] = n * 256 + (((2 * ks + h) ^ x) << 4);
         const int i = lane & 15, nh = (lane >> 4) & 1, j4 = i >> 2;
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb)
@@ -300,7 +302,7 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) s_a[r] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) s_a = mfma(lds_read_b128(k_lds0, k_step_addr<TRI>(kaddr, ks)), qf[ks], s_a);
+        for (int ks = 0; ks < 8; ++ks) s_a = mfma(lds_read_b128(k_lds0, k_step_addr(kaddr, ks)), qf[ks], s_a);
     }
 
     // Trip t = iterations u = 2t and 2t+1 with barrier t between them.  Iteration u does
@@ -310,72 +312,65 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     //              requested at barrier t-1, have landed
     //   u = 2t+1: QK(2t+2): K tile t+1, first half     PV(2t): V tile t, first half
     // PAR = t & 1 fixes every LDS offset at compile time.
-    // HOT: a trip of the hot loop, where tiles t + 1 and t + 2 always exist
-    auto trip = [&](auto first_c, auto last_c, auto mask_c, auto par_c, int t, auto hot_c) __attribute__((always_inline)) {
+    // LD: which of the two tile requests of the trip exist: 2 = K(t+2) and V(t+1), 1 = V(t+1)
+    // only (the last trip but one), 0 = none (the last trip)
+    auto trip = [&](auto first_c, auto last_c, auto mask_c, auto par_c, int t, auto ld_c) __attribute__((always_inline)) {
         constexpr bool FIRST = decltype(first_c)::value, LAST = decltype(last_c)::value;
-        constexpr bool MASK = decltype(mask_c)::value, HOT = decltype(hot_c)::value;
-        constexpr int PAR = decltype(par_c)::value;
+        constexpr bool MASK = decltype(mask_c)::value;
+        constexpr int PAR = decltype(par_c)::value, LD = decltype(ld_c)::value;
         char* const k_cur = PAR ? k_lds1 : k_lds0;
         char* const k_nxt = PAR ? k_lds0 : k_lds1;
         char* const v_cur = PAR ? v_lds1 : v_lds0;
         char* const v_prv = PAR ? v_lds0 : v_lds1;
-        step<true, true, !FIRST, MASK, TRI>(s_a, s_b, p_a, p_b, oacc, qf, m, l, kappa, kaddr, vaddr,
+        step<true, true, !FIRST, MASK>(s_a, s_b, p_a, p_b, oacc, qf, m, l, kappa, kaddr, vaddr,
                                        k_cur + TILE_BYTES / 2, v_prv + TILE_BYTES / 2, mask_base - 64 * t);
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-        if (HOT || t + 2 < n_kt) load_tile_direct(K, (t + 2) * tile_pitch, k_cur, kg0, wave, pitch);
-        if (HOT || t + 1 < n_kt) load_v_tile_direct(V, (t + 1) * tile_pitch, v_prv, vg0, wave, pitch);
-        step<!LAST, true, true, MASK, TRI>(s_b, s_a, p_b, p_a, oacc, qf, m, l, kappa, kaddr, vaddr, k_nxt, v_cur,
+        if (LD >= 2) load_tile_direct(K, (t + 2) * tile_pitch, k_cur, kg0, wave, pitch);
+        if (LD >= 1) load_v_tile_direct(V, (t + 1) * tile_pitch, v_prv, vg0, wave, pitch);
+        step<!LAST, true, true, MASK>(s_b, s_a, p_b, p_a, oacc, qf, m, l, kappa, kaddr, vaddr, k_nxt, v_cur,
                                       mask_base - 64 * t - 32);
     };
     using T = std::true_type;
     using F = std::false_type;
     using P0 = std::integral_constant<int, 0>;
     using P1 = std::integral_constant<int, 1>;
-    // run trip t with its first / last / parity flags resolved at run time (n_kt >= 2, so a
-    // trip is never both first and last)
-    auto run = [&](auto mask_c, int t) __attribute__((always_inline)) {
-        const bool last = t + 1 == n_kt;
-        if (t & 1) {
-            if (last) trip(F{}, T{}, mask_c, P1{}, t, F{});
-            else trip(F{}, F{}, mask_c, P1{}, t, F{});
-        } else if (t == 0) {
-            trip(T{}, F{}, mask_c, P0{}, t, F{});
-        } else if (last) {
-            trip(F{}, T{}, mask_c, P0{}, t, F{});
+    using L0 = std::integral_constant<int, 0>;
+    using L1 = std::integral_constant<int, 1>;
+    using L2 = std::integral_constant<int, 2>;
+    // The number of trips is even (tiles come in pairs of 64 keys per 128-row block), so the
+    // walk is a sequence of (even, odd) pairs of fixed form: the first pair, plain pairs (the
+    // hot loop), masked pairs, the last pair.  Triangular steps: the trips from t_mask on carry
+    // the element mask (the last BM / 64 ones, more under emulated coarse skipping).
+    const int t_mask = n_kt_fine - BM / TILE_ROWS;
+    if (n_kt == 2) {                   // a single pair (triangular: the first query tile)
+        trip(T{}, F{}, T{}, P0{}, 0, L1{});
+        trip(F{}, T{}, T{}, P1{}, 1, L0{});
+    } else {
+        if (t_mask == 0) {      // masked from the start (emulated coarse skipping only)
+            trip(T{}, F{}, T{}, P0{}, 0, L2{});
+            trip(F{}, F{}, T{}, P1{}, 1, L2{});
         } else {
-            trip(F{}, F{}, mask_c, P0{}, t, F{});
+            trip(T{}, F{}, F{}, P0{}, 0, L2{});
+            trip(F{}, F{}, F{}, P1{}, 1, L2{});
         }
-    };
-    // triangular steps: the trips from the diagonal on carry the element mask (the last
-    // BM / 64 ones, more under emulated coarse skipping)
-    const int t_mask = TRI ? n_kt_fine - BM / TILE_ROWS : n_kt;
-    const int t_hot = TRI ? t_mask : n_kt - 1;       // plain, neither first nor last: [1, t_hot)
-    int t = 0;
-    if (t_mask > 0) {
-        run(F{}, 0);
-        for (t = 1; t + 1 < t_hot; t += 2) {          // the hot loop: two plain trips per turn
-            trip(F{}, F{}, F{}, P1{}, t, T{});         // t + 3 < t_hot + 2 <= n_kt
-            trip(F{}, F{}, F{}, P0{}, t + 1, T{});
+        int t = 2;
+        const int t_plain = min(t_mask, n_kt - 2);
+        for (; t < t_plain; t += 2) {                  // the hot loop: two plain trips per turn
+            trip(F{}, F{}, F{}, P0{}, t, L2{});
+            trip(F{}, F{}, F{}, P1{}, t + 1, L2{});
         }
-        for (; t < t_mask; ++t) run(F{}, t);
+        for (; t < n_kt - 2; t += 2) {                 // masked pairs before the last one
+            trip(F{}, F{}, T{}, P0{}, t, L2{});
+            trip(F{}, F{}, T{}, P1{}, t + 1, L2{});
+        }
+        trip(F{}, F{}, T{}, P0{}, n_kt - 2, L1{});    // the last pair always carries the mask
+        trip(F{}, T{}, T{}, P1{}, n_kt - 1, L0{});
     }
-    // masked trips; under emulated coarse skipping there are many, so pairs of them that are
-    // neither first nor last take the same fixed-parity form as the hot loop
-    if (TRI)
-        for (; t < n_kt; ++t) {
-            if (!(t & 1) && t > 0 && t + 3 < n_kt) {
-                trip(F{}, F{}, T{}, P0{}, t, T{});
-                trip(F{}, F{}, T{}, P1{}, t + 1, T{});
-                ++t;
-            } else {
-                run(T{}, t);
-            }
-        }
     // final iteration u = 2 n_kt: PV(2 n_kt - 1): V tile n_kt - 1, second half; P in p_b
     {
-        const char* v_last = (((n_kt - 1) & 1) ? v_lds1 : v_lds0) + TILE_BYTES / 2;
-        step<false, false, true, false, TRI>(s_a, s_b, p_a, p_b, oacc, qf, m, l, kappa, kaddr, vaddr, v_last, v_last, 0);
+        const char* v_last = v_lds1 + TILE_BYTES / 2;          // n_kt - 1 is odd
+        step<false, false, true, false>(s_a, s_b, p_a, p_b, oacc, qf, m, l, kappa, kaddr, vaddr, v_last, v_last, 0);
     }
 
     // epilogue: normalise, store the merged state
@@ -409,8 +404,6 @@ hipError_t launch_fwd_mfma(const StepArgs& a, hipStream_t st) {
     const int n_qtiles = (a.c + BM - 1) / BM;
     const dim3 grid(n_qtiles * a.B * a.H), block(64 * NW);
     if (a.c % BM)
-        hipLaunchKernelGGL((fwd_mfma_kernel<true, true>), grid, block, 0, st, a, n_qtiles);
-    else if (a.kind == MASK_TRI)
         hipLaunchKernelGGL((fwd_mfma_kernel<true>), grid, block, 0, st, a, n_qtiles);
     else
         hipLaunchKernelGGL((fwd_mfma_kernel<false>), grid, block, 0, st, a, n_qtiles);
