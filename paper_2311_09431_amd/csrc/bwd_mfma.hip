@@ -94,10 +94,12 @@ __device__ inline void dq_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, f3
     }
 }
 
-// RAGGED (c not a multiple of 128), as in the forward kernel: loads of rows beyond the shard
-// are clamped, their results are not stored, keys beyond it come in as zero rows and are
-// removed by the element mask (full blocks: mask limit c - 1); implies the triangular path.
-template <bool TRI, bool RAGGED = false>
+// One code path serves triangular and full blocks, as in the forward kernel: the last two
+// tiles of the walk carry the element mask, whose limit is the query's own position, or the
+// last key (c - 1) for a full block.  RAGGED (c not a multiple of 128): loads of rows beyond
+// the shard are clamped, their results are not stored, keys beyond it come in as zero rows
+// and are removed by the mask.
+template <bool RAGGED>
 __global__ void __launch_bounds__(256, 2)
 bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
     // one LDS object per tile buffer
@@ -110,7 +112,7 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform, kept scalar
     int rank, bh;
     decode_block<true>((int)blockIdx.x, n_tiles, p.B * p.H, rank, bh);
-    const int qt = TRI ? n_tiles - 1 - rank : rank;      // heaviest query tiles first
+    const int qt = n_tiles - 1 - rank;      // heaviest query tiles first
     const int b = bh / p.H, hd = bh - b * p.H;
     const int64_t base = b * p.stride_b + hd * p.stride_h;
     // key/value head of this query head's group (the same head when H_kv == H)
@@ -129,12 +131,12 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
     const int q0 = qt * BM, a_own = q0 + 32 * wave + n;
     const bool row_ok = !RAGGED || a_own < p.c;
     const int a = RAGGED ? min(a_own, p.c - 1) : a_own;      // the row this lane loads
-    const bool full_block = RAGGED && p.kind == MASK_FULL;   // a full block on the masked code path
+    const bool full_block = p.kind == MASK_FULL;     // every key allowed: the mask limit is the last key
     // all four wavefronts walk the 2 n_kt sub-tiles of the workgroup (at most three are
     // entirely masked for a wavefront); the element mask runs on the last four only
-    const int n_kt_fine = TRI ? (full_block ? 2 * n_tiles : (q0 + BM) / DT_ROWS) : p.c / DT_ROWS;
+    const int n_kt_fine = full_block ? 2 * n_tiles : (q0 + BM) / DT_ROWS;
     int n_kt = n_kt_fine;
-    if (TRI && p.skip_bq > 0) {       // emulated coarse skipping, as in the forward kernel
+    if (!full_block && p.skip_bq > 0) {       // emulated coarse skipping, as in the forward kernel
         const int q_hi = (q0 / p.skip_bq + 1) * p.skip_bq - 1;
         n_kt = min(p.c, ((q_hi - p.off) / p.skip_bk + 1) * p.skip_bk) / DT_ROWS;
     }
@@ -208,32 +210,19 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
     using F = std::false_type;
     using P0 = std::integral_constant<int, 0>;
     using P1 = std::integral_constant<int, 1>;
+    // trips before the last tile pair of the fine walk without the element mask, then masked
+    // trips: two, more under emulated coarse skipping (n_kt_fine and n_kt are even)
     int t = 0;
-    if (TRI) {
-        // trips before the diagonal without the element mask, then masked trips: two, more
-        // under emulated coarse skipping (n_kt_fine and n_kt are even)
-        for (; t + 2 < n_kt_fine; t += 2) {
-            trip(F{}, F{}, P0{}, t);
-            trip(F{}, F{}, P1{}, t + 1);
-        }
-        for (; t + 2 < n_kt; t += 2) {
-            trip(F{}, T{}, P0{}, t);
-            trip(F{}, T{}, P1{}, t + 1);
-        }
-        trip(F{}, T{}, P0{}, t);
-        trip(T{}, T{}, P1{}, t + 1);
-    } else {
-        for (; t + 2 < n_kt; t += 2) {
-            trip(F{}, F{}, P0{}, t);
-            trip(F{}, F{}, P1{}, t + 1);
-        }
-        if (t + 1 < n_kt) {
-            trip(F{}, F{}, P0{}, t);
-            trip(T{}, F{}, P1{}, t + 1);
-        } else {
-            trip(T{}, F{}, P0{}, t);
-        }
+    for (; t + 2 < n_kt_fine; t += 2) {
+        trip(F{}, F{}, P0{}, t);
+        trip(F{}, F{}, P1{}, t + 1);
     }
+    for (; t + 2 < n_kt; t += 2) {
+        trip(F{}, T{}, P0{}, t);
+        trip(F{}, T{}, P1{}, t + 1);
+    }
+    trip(F{}, T{}, P0{}, t);
+    trip(T{}, T{}, P1{}, t + 1);
 
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb)
@@ -554,8 +543,6 @@ hipError_t launch_bwd_mfma(const StepArgs& a, hipStream_t st) {
     const bool ragged = a.c % BM != 0;
     const dim3 grid_q(n_tiles * a.B * a.H), grid_kv(n_tiles * a.B * a.H_kv), block(256);
     if (ragged)
-        hipLaunchKernelGGL((bwd_dq_mfma_kernel<true, true>), grid_q, block, 0, st, a, n_tiles);
-    else if (a.kind == MASK_TRI)
         hipLaunchKernelGGL((bwd_dq_mfma_kernel<true>), grid_q, block, 0, st, a, n_tiles);
     else
         hipLaunchKernelGGL((bwd_dq_mfma_kernel<false>), grid_q, block, 0, st, a, n_tiles);
