@@ -37,9 +37,9 @@ PEAK_HBM_GBS = 8000.0
 TRAFFIC = {
     "cfg3": {
         "fwd ring step (fwd_mfma_kernel)":
-            {"read_GB": 3.85, "written_GB": 0.96, "algorithmic_GB": 1.89},
+            {"read_GB": 3.67, "written_GB": 0.84, "algorithmic_GB": 1.89},
         "bwd ring step (bwd_dq_mfma_kernel + bwd_dkdv_mfma_kernel)":
-            {"read_GB": 8.05, "written_GB": 1.61, "algorithmic_GB": 5.37},
+            {"read_GB": 8.12, "written_GB": 1.61, "algorithmic_GB": 5.37},
     },
 }
 

@@ -99,7 +99,9 @@ __device__ inline void dq_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, f3
 // last key (c - 1) for a full block.  RAGGED (c not a multiple of 128): loads of rows beyond
 // the shard are clamped, their results are not stored, keys beyond it come in as zero rows
 // and are removed by the mask.
-template <bool RAGGED>
+// (FULL is a template argument rather than a launch argument so that profiler traces name
+// triangular and full launches apart; the code is the same.)
+template <bool RAGGED, bool FULL>
 __global__ void __launch_bounds__(256, 2)
 bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
     // one LDS object per tile buffer
@@ -131,7 +133,7 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
     const int q0 = qt * BM, a_own = q0 + 32 * wave + n;
     const bool row_ok = !RAGGED || a_own < p.c;
     const int a = RAGGED ? min(a_own, p.c - 1) : a_own;      // the row this lane loads
-    const bool full_block = p.kind == MASK_FULL;     // every key allowed: the mask limit is the last key
+    constexpr bool full_block = FULL;                // every key allowed: the mask limit is the last key
     // all four wavefronts walk the 2 n_kt sub-tiles of the workgroup (at most three are
     // entirely masked for a wavefront); the element mask runs on the last four only
     const int n_kt_fine = full_block ? 2 * n_tiles : (q0 + BM) / DT_ROWS;
@@ -542,10 +544,14 @@ hipError_t launch_bwd_mfma(const StepArgs& a, hipStream_t st) {
     const int n_tiles = (a.c + BM - 1) / BM;
     const bool ragged = a.c % BM != 0;
     const dim3 grid_q(n_tiles * a.B * a.H), grid_kv(n_tiles * a.B * a.H_kv), block(256);
-    if (ragged)
-        hipLaunchKernelGGL((bwd_dq_mfma_kernel<true>), grid_q, block, 0, st, a, n_tiles);
-    else
-        hipLaunchKernelGGL((bwd_dq_mfma_kernel<false>), grid_q, block, 0, st, a, n_tiles);
+    const bool full = a.kind == MASK_FULL;
+    if (ragged) {
+        if (full) hipLaunchKernelGGL((bwd_dq_mfma_kernel<true, true>), grid_q, block, 0, st, a, n_tiles);
+        else hipLaunchKernelGGL((bwd_dq_mfma_kernel<true, false>), grid_q, block, 0, st, a, n_tiles);
+    } else {
+        if (full) hipLaunchKernelGGL((bwd_dq_mfma_kernel<false, true>), grid_q, block, 0, st, a, n_tiles);
+        else hipLaunchKernelGGL((bwd_dq_mfma_kernel<false, false>), grid_q, block, 0, st, a, n_tiles);
+    }
     hipError_t e = hipGetLastError();
     // dK, dV: the members of a group of query heads one after the other, each adding to the
     // shared head's accumulators in stream order (deterministic)

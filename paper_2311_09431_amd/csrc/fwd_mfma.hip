@@ -198,7 +198,9 @@ __device__ inline void step(f32x16& s_cur, f32x16& s_next, bf16x8 (&p_cur)[2], b
 // the shard (their loads are clamped to the last row, their results are not stored) and the
 // last key tiles hold keys beyond it (the tile loads return zeros there and the mask removes
 // them).
-template <bool RAGGED>
+// (FULL is a template argument rather than a launch argument so that profiler traces name
+// triangular and full launches apart; the code is the same.)
+template <bool RAGGED, bool FULL>
 __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1)
 fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     // one LDS object per tile buffer
@@ -230,7 +232,7 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     const int a_own = q0 + 32 * wave + n;     // this lane's query row
     const bool row_ok = !RAGGED || a_own < p.c;
     const int a = RAGGED ? min(a_own, p.c - 1) : a_own;      // the row it loads
-    const bool full_block = p.kind == MASK_FULL;     // every key allowed: the mask limit is the last key
+    constexpr bool full_block = FULL;                // every key allowed: the mask limit is the last key
     // 64-key tiles holding at least one allowed pair for the workgroup.  Triangular: keys
     // b <= a - off, i.e. tiles 0 .. (q0 + 127) / 64.  All four wavefronts walk all 2 n_kt
     // sub-tiles (at most NW - 1 of them are entirely masked for a wavefront); the element
@@ -403,10 +405,14 @@ bool fwd_mfma_supported(const StepArgs& a, int dtype) {
 hipError_t launch_fwd_mfma(const StepArgs& a, hipStream_t st) {
     const int n_qtiles = (a.c + BM - 1) / BM;
     const dim3 grid(n_qtiles * a.B * a.H), block(64 * NW);
-    if (a.c % BM)
-        hipLaunchKernelGGL((fwd_mfma_kernel<true>), grid, block, 0, st, a, n_qtiles);
-    else
-        hipLaunchKernelGGL((fwd_mfma_kernel<false>), grid, block, 0, st, a, n_qtiles);
+    const bool full = a.kind == MASK_FULL;
+    if (a.c % BM) {
+        if (full) hipLaunchKernelGGL((fwd_mfma_kernel<true, true>), grid, block, 0, st, a, n_qtiles);
+        else hipLaunchKernelGGL((fwd_mfma_kernel<true, false>), grid, block, 0, st, a, n_qtiles);
+    } else {
+        if (full) hipLaunchKernelGGL((fwd_mfma_kernel<false, true>), grid, block, 0, st, a, n_qtiles);
+        else hipLaunchKernelGGL((fwd_mfma_kernel<false, false>), grid, block, 0, st, a, n_qtiles);
+    }
     return hipGetLastError();
 }
 
