@@ -127,14 +127,10 @@ __device__ inline void step(f32x16& s_cur, f32x16& s_next, bf16x8 (&p_cur)[2], b
     };
     fetch(0);
     fetch(1);
-    float m_use = 0.f;
-    if (SM) {
-        if (MASK) {
+    if (SM && MASK) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r)
-                if (8 * (r / 4) + (r % 4) > mask_lim) s_cur[r] = -INFINITY;
-        }
-        m_use = (m == -INFINITY) ? 0.f : m;        // row with no key so far
+        for (int r = 0; r < 16; ++r)
+            if (8 * (r / 4) + (r % 4) > mask_lim) s_cur[r] = -INFINITY;
     }
     if (QK) {
 #pragma unroll
@@ -148,8 +144,8 @@ __device__ inline void step(f32x16& s_cur, f32x16& s_next, bf16x8 (&p_cur)[2], b
         if (QK) s_next = mfma(ka[i], qf[i], s_next);
         if (PV) oacc[i % 4] = mfma(va[i], p_prev[i / 4], oacc[i % 4]);
         if (SM) {
-            const float p0 = __builtin_amdgcn_exp2f(fmaf(s_cur[2 * i], kappa, -m_use));
-            const float p1 = __builtin_amdgcn_exp2f(fmaf(s_cur[2 * i + 1], kappa, -m_use));
+            const float p0 = __builtin_amdgcn_exp2f(fmaf(s_cur[2 * i], kappa, -m));
+            const float p1 = __builtin_amdgcn_exp2f(fmaf(s_cur[2 * i + 1], kappa, -m));
             rs0 += p0;
             rs1 += p1;
             p_cur[i / 4][(2 * i) % 8] = (__bf16)p0;
@@ -162,15 +158,16 @@ __device__ inline void step(f32x16& s_cur, f32x16& s_next, bf16x8 (&p_cur)[2], b
         // The probabilities above were taken against the reference as it stood, without looking
         // at the scores first.  That is exact as long as nothing overflows (a floating-point
         // sum does not care about a common factor), so the reference only has to move when a
-        // row's partial sum grows out of hand, or when the row has no reference yet; then the
-        // sub-tile is redone against the row maximum.  Wave-uniform and rare.
-        if (__builtin_amdgcn_ballot_w64(!(rs < RESCALE_SUM) || m == -INFINITY) != 0) {
+        // row's partial sum grows out of hand, or when the row has no reference yet (m = -inf
+        // makes every term above +inf or NaN, so the same test catches it); then the sub-tile
+        // is redone against the row maximum.  Wave-uniform and rare.
+        if (__builtin_amdgcn_ballot_w64(!(rs < RESCALE_SUM)) != 0) {
             float mx = fmaxf(s_cur[0], s_cur[1]);
 #pragma unroll
             for (int r = 2; r < 16; ++r) mx = fmaxf(mx, s_cur[r]);
             mx = half_wave_max(mx);
             const float m_new = fmaxf(m, mx * kappa);
-            m_use = (m_new == -INFINITY) ? 0.f : m_new;
+            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;     // row with no key so far
             const float alpha = __builtin_amdgcn_exp2f(m - m_use);
             m = m_new;
             l *= alpha;
