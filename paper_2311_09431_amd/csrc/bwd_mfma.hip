@@ -16,7 +16,9 @@
 //    ONE key in a lane; P and dS are the B operands of dV^T += dO^T P and
 //    dK^T += Q^T dS.
 // Both skip every tile the mask empties (Sec. 2.2.1) per 32-row wavefront and
-// apply the element mask only on tiles that cross the diagonal.
+// apply the element mask only on the tiles that can cross the diagonal (the dq
+// kernel also on the last tile pair of a full block, where it removes nothing
+// unless the block size is not a multiple of 128).
 #include <hip/hip_bf16.h>
 
 #include <type_traits>
