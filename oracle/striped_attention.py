@@ -20,7 +20,8 @@ N devices, block size c = n_seq / N, query device j, key/value device k.
 
 Pinned by tests/test_oracle_*.py against: brute-force S x S softmax with the
 mask matrix C, closed forms (Q = 0, V = 1, first row), a library causal SDPA
-and library autograd in fp64, central finite differences, the paper's printed
+and library autograd in fp64, central finite differences (the matrix-form gradient over a row set also against
+the row-by-row one), the paper's printed
 stripe example, its Work(i, j) formula and its tiling examples; the grouped-head
 functions (fewer key/value heads, an extension) against the library's grouped
 attention and autograd, repeated heads and finite differences.
@@ -95,6 +96,43 @@ def causal_attention_grad(Q, K, V, dO, scale, rows=None):
         dQ[i] = scale * (ds @ K[: i + 1])
         dK[: i + 1] += scale * np.outer(ds, Q[i])
     return dQ, dK, dV
+
+
+def causal_attention_grad_matrix(Q, K, V, dO, scale, rows):
+    """The same gradient for a set of query rows, in the matrix form of Sec. 2.1.
+
+    With R = `rows` (dO is treated as zero outside R): S = scale Q_R K^T + C_R is formed whole
+    (|R| rows; the columns after the last row of R, which C masks for all of R, are left
+    out), P = Softmax(S) row-wise, O_R = P V, dV = P^T dO_R, dP = dO_R V^T,
+    dS = P * (dP - rowsum(dO_R * O_R)), dQ_R = scale dS K, dK = scale dS^T Q_R.
+    Nothing is blocked: memory is a few |R| x n_seq float64 matrices, so callers keep |R|
+    moderate (the gradient is additive over disjoint row sets).  Also returns O_R and LSE_R.
+    Since dQ_i depends on row i of dO only, dQ[R] is also the dense-dO answer for those rows.
+    """
+    Q = np.asarray(Q, np.float64)
+    K = np.asarray(K, np.float64)
+    V = np.asarray(V, np.float64)
+    dO = np.asarray(dO, np.float64)
+    rows = np.asarray(rows, np.int64)
+    n = int(rows.max()) + 1      # keys at later positions are masked for every row of R: left out
+    K, V = K[:n], V[:n]
+    S = scale * (Q[rows] @ K.T)
+    S[np.arange(n)[None, :] > rows[:, None]] = -np.inf      # C[i, j] = -inf iff i < j
+    m = S.max(axis=1, keepdims=True)
+    P = np.exp(S - m)
+    l = P.sum(axis=1, keepdims=True)
+    P /= l
+    O = P @ V
+    g = dO[rows]
+    dV = P.T @ g
+    dS = P * (g @ V.T - (g * O).sum(axis=1, keepdims=True))
+    dQ = np.zeros_like(Q)
+    dQ[rows] = scale * (dS @ K)
+    dK = np.zeros_like(Q)
+    dK[:n] = scale * (dS.T @ Q[rows])
+    dVf = np.zeros((Q.shape[0], V.shape[1]))
+    dVf[:n] = dV
+    return dQ, dK, dVf, O, (m + np.log(l))[:, 0]
 
 
 def _map_bh(fn, n_out, *arrays):
@@ -238,32 +276,6 @@ def get_mask(j, k, N, c, layout):
     a = np.arange(c)[:, None]
     b = np.arange(c)[None, :]
     return global_position(k, b, N, c, layout) <= global_position(j, a, N, c, layout)
-
-
-def get_mask_listing(j, k, c, layout):
-    """The GetMask procedures of Sec. 2.2 and 2.3 as this build reads them,
-    written in local indices a (query) and b (key).
-
-    The printed listings index MASK[x, y] with x the key index and y the query
-    index (with that reading the striped listing agrees with Work(i, j) and the
-    ring listing selects block (j, k) of C, as the text after it says).  Ring:
-    j < k all masked, j = k masked where a < b, j > k nothing masked.  Striped:
-    j < k masked where a <= b, j >= k masked where a < b.
-    Returns allowed[a, b] (True = not masked).
-    """
-    a = np.arange(c)[:, None]
-    b = np.arange(c)[None, :]
-    if layout == CONTIGUOUS:
-        if j < k:
-            return np.zeros((c, c), bool)
-        if j == k:
-            return ~(a < b)
-        return np.ones((c, c), bool)
-    if layout == STRIPED:
-        if j < k:
-            return ~(a <= b)
-        return ~(a < b)
-    raise ValueError("unknown layout")
 
 
 def work(j, k, N, c, layout):

@@ -56,6 +56,21 @@ def max_abs_err(a, b):
     return float(np.max(np.abs(np.asarray(a, np.float64) - np.asarray(b, np.float64))))
 
 
+def check_grad(name, got, want, bf16):
+    """Gradient criteria shared by the parity tests: max abs error <= 2e-2 (bf16) or 2e-5
+    (fp32) times max(1, max|want|), and ||got - want||_F <= 1e-2 (2e-5) ||want||_F, which
+    does not loosen with the gradient's magnitude (bf16 rounding of P and dS is about 1e-3
+    rms of every term; a dropped tile or term is of order one)."""
+    got = np.asarray(got, np.float64)
+    assert got.shape == want.shape and np.isfinite(got).all(), name
+    err = max_abs_err(got, want)
+    assert err <= (2e-2 if bf16 else 2e-5) * max(1.0, float(np.max(np.abs(want)))), (name, err)
+    den = float(np.linalg.norm(want))
+    if den > 0:
+        rel = float(np.linalg.norm(got - want)) / den
+        assert rel <= (1e-2 if bf16 else 2e-5), (name, "relative", rel)
+
+
 def ring_backward_gpu(Q, K, V, dO, N, layout, scale=None, use_driver=False):
     """Forward ring, then all N*N backward steps.  Inputs in ORIGINAL order on the
     GPU; returns (dQ, dK, dV) fp32 GPU tensors in device order."""

@@ -29,6 +29,7 @@ def _check(B, H, S, d, N, layout, dtype, seed, use_driver=False):
         assert np.isfinite(gh).all()
         err = hp.max_abs_err(gh, w)
         assert err <= _tolerance(dtype, w), (name, err, hp.layout_name(layout))
+        hp.check_grad(name + " " + hp.layout_name(layout), gh, w, dtype != torch.float32)
 
 
 @pytest.mark.parametrize("layout", [sa.CONTIGUOUS, sa.STRIPED])

@@ -74,3 +74,52 @@ def test_rows_subset_equals_zeroed_dout():
     mask = np.ones(21, bool)
     mask[rows] = False
     assert np.all(a[0][mask] == 0)
+
+
+@pytest.mark.parametrize("S,d,rows", [
+    (21, 4, [0, 5, 6, 20]),
+    (40, 8, list(range(40))),
+    (33, 5, [32]),
+    (17, 3, [3, 16, 9]),           # unsorted
+])
+def test_matrix_form_over_a_row_set_equals_the_row_by_row_gradient(S, d, rows):
+    Q, K, V, dO = _rand(S, d, 14 + S)
+    a = orc.causal_attention_grad(Q, K, V, dO, 0.7, rows=rows)
+    dQ, dK, dV, O, LSE = orc.causal_attention_grad_matrix(Q, K, V, dO, 0.7, rows)
+    for x, y in zip(a, (dQ, dK, dV)):
+        np.testing.assert_allclose(x, y, atol=1e-13)
+    Ow, Lw = orc.causal_attention_rows(Q, K, V, 0.7, rows)
+    np.testing.assert_allclose(O, Ow, atol=1e-13)
+    np.testing.assert_allclose(LSE, Lw, atol=1e-13)
+
+
+def test_matrix_form_finite_differences_and_additivity():
+    S, d, scale = 10, 3, 0.9
+    Q, K, V, dO = _rand(S, d, 99)
+    rows = [2, 7, 9]
+    dOz = np.zeros_like(dO)
+    dOz[rows] = dO[rows]
+    grads = orc.causal_attention_grad_matrix(Q, K, V, dO, scale, rows)[:3]
+    eps = 1e-6
+    for which, g in enumerate(grads):
+        num = np.zeros_like(g)
+        for idx in np.ndindex(*g.shape):
+            args = [Q.copy(), K.copy(), V.copy()]
+            args[which][idx] += eps
+            up = _loss(*args, dOz, scale)
+            args[which][idx] -= 2 * eps
+            dn = _loss(*args, dOz, scale)
+            num[idx] = (up - dn) / (2 * eps)
+        np.testing.assert_allclose(g, num, atol=2e-8, rtol=1e-7)
+    # additive over disjoint row sets; dQ rows do not depend on the other rows' dO
+    a = orc.causal_attention_grad_matrix(Q, K, V, dO, scale, [2, 7])
+    b = orc.causal_attention_grad_matrix(Q, K, V, dO, scale, [9])
+    for x, y, z in zip(a[:3], b[:3], grads):
+        np.testing.assert_allclose(x + y, z, atol=1e-14)
+    full = orc.causal_attention_grad(Q, K, V, dO, scale)
+    np.testing.assert_allclose(grads[0][rows], full[0][rows], atol=1e-14)
+    # keys at or after position j0 are seen only by queries at or after j0
+    j0 = 6
+    tail = orc.causal_attention_grad_matrix(Q, K, V, dO, scale, list(range(j0, S)))
+    np.testing.assert_allclose(tail[1][j0:], full[1][j0:], atol=1e-14)
+    np.testing.assert_allclose(tail[2][j0:], full[2][j0:], atol=1e-14)

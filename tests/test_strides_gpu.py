@@ -80,8 +80,7 @@ def test_seq_major_forward_and_backward(layout, B, H, S, d, N, dtype, use_driver
     assert hp.max_abs_err(hp.from_device_order_host(LSE.cpu().numpy(), N, layout), Lref) <= (1e-3 if bf16 else 1e-5)
     assert hp.max_abs_err(back(out), Oref) <= (3e-2 if bf16 else 1e-5)      # one more bf16 rounding
     for g, w in zip(grads, gref):
-        tol = (2e-2 if bf16 else 2e-5) * max(1.0, float(np.max(np.abs(w))))
-        assert hp.max_abs_err(back(g), w) <= tol
+        hp.check_grad("gradient", back(g), w, bf16)
 
 
 def test_rows_that_overlap_are_rejected():
