@@ -18,6 +18,7 @@ Prints one JSON line.
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -31,17 +32,32 @@ from paper_2311_09431_amd import inputs           # noqa: E402
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
-# HBM bytes per launch (one triangular step of the cfg3 workload) measured with rocprofv3 --pmc
-# FETCH_SIZE (x2, calibrated on the copy kernel) and WRITE_SIZE, see
-# profiles/ring_step_kernels_cfg3.txt; only valid for that workload
-TRAFFIC = {
-    "cfg3": {
-        "fwd ring step (fwd_mfma_kernel)":
-            {"read_GB": 3.67, "written_GB": 0.84, "algorithmic_GB": 1.89},
-        "bwd ring step (bwd_dq_mfma_kernel + bwd_dkdv_mfma_kernel)":
-            {"read_GB": 8.12, "written_GB": 1.61, "algorithmic_GB": 5.37},
-    },
+# kernels of each family, as rocprofv3 names them
+FAMILIES = {
+    "fwd": ("fwd ring step (fwd_mfma_kernel)", ("fwd_mfma_kernel",)),
+    "bwd": ("bwd ring step (bwd_dq_mfma_kernel + bwd_dkdv_mfma_kernel)",
+            ("bwd_dq_mfma_kernel", "bwd_dkdv_mfma_kernel")),
 }
+
+
+def measured_traffic(workload):
+    """HBM bytes per launch of a triangular step, read from the committed rocprofv3 summary of
+    this workload (profiles/ring_step_kernels_<workload>.txt): lines of the form
+        TRAFFIC <kernel> read_GB=<x> written_GB=<y>
+    written there from the FETCH_SIZE / WRITE_SIZE counter runs.  Returns {kernel: (read, written)};
+    empty when there is no summary for the workload, so a stale figure is never reported."""
+    path = os.path.join(ROOT, "profiles", "ring_step_kernels_%s.txt" % workload)
+    out = {}
+    try:
+        with open(path) as f:
+            for line in f:
+                t = line.split()
+                if len(t) == 4 and t[0] == "TRAFFIC" and t[2].startswith("read_GB=") and t[3].startswith("written_GB="):
+                    out[t[1]] = (float(t[2].split("=")[1]), float(t[3].split("=")[1]))
+    except (OSError, ValueError):
+        return {}
+    return out
+
 
 # one device's share: the worst-loaded query device of both layouts is N-1
 WORKLOADS = {
@@ -182,8 +198,8 @@ def hbm_bound_kernels(run, reps=5):
     return out
 
 
-def summarize_steps(w, layout, table, per_pair, table_min=None):
-    """Per-step latency (mean over the timed passes, and the fastest pass if table_min is given)
+def summarize_steps(w, layout, table, per_pair, table_min=None, table_med=None):
+    """Per-step latency (mean over the timed passes; the fastest pass and the median if given)
     / TFLOP/s rows and the worst-device latency of every round."""
     N = w["N"]
     rows, worst = [], []
@@ -197,14 +213,18 @@ def summarize_steps(w, layout, table, per_pair, table_min=None):
                              tflops=round(fl / (ms * 1e9), 1) if ms > 0 else 0.0))
             if table_min is not None:
                 rows[-1]["ms_min"] = round(table_min[i][j], 4)
+            if table_med is not None:
+                rows[-1]["ms_median"] = round(table_med[i][j], 4)
             ms_round = max(ms_round, ms)
         worst.append(round(ms_round, 4))
     return rows, worst
 
 
-def cpu_baseline(seconds_budget=20.0):
-    """The fp64 oracle, as it stands, on a bounded sample of the same workload
-    shape: one head of d = 128 at a sequence length it finishes in ~10-30 s."""
+def cpu_baseline():
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload shape: one head of
+    d = 128, the forward at a sequence length it finishes in ~10 s and the gradient (row by row,
+    much slower per pair) at one it finishes in ~20 s.  `value` is the useful causal rate of
+    forward + backward together, as the GPU figure is."""
     import numpy as np
     from oracle import striped_attention as orc
     try:
@@ -212,30 +232,44 @@ def cpu_baseline(seconds_budget=20.0):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = 1
-    S, d = 49152, 128
-    q, k, v = (inputs.to_f64(x)[0, 0] for x in inputs.qkv(1, 1, S, d, 99, torch.bfloat16))
+    d, S_f, S_b = 128, 32768, 6144
+    scale = 1.0 / np.sqrt(d)
+    q, k, v, g = (inputs.to_f64(x)[0, 0] for x in inputs.qkv(1, 1, S_f, d, 99, torch.bfloat16, with_dout=True))
     t0 = time.perf_counter()
-    orc.causal_attention(q, k, v, 1.0 / np.sqrt(d))
-    dt = time.perf_counter() - t0
-    flops = S * (S + 1) // 2 * 4 * d
-    return dict(value=flops / dt / 1e12, unit="TFLOP/s (useful causal, fp64)", cores=cores,
-                kind="oracle", seconds=round(dt, 2),
-                sample="oracle.causal_attention on 1 head, d=128, S=%d (%.1f GFLOP useful), forward" %
-                       (S, flops / 1e9))
+    orc.causal_attention(q, k, v, scale)
+    t_f = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    orc.causal_attention_grad(q[:S_b], k[:S_b], v[:S_b], g[:S_b], scale)
+    t_b = time.perf_counter() - t0
+    fl_f = S_f * (S_f + 1) // 2 * 4 * d
+    fl_b = S_b * (S_b + 1) // 2 * 10 * d
+    return dict(value=(fl_f + fl_b) / (t_f + t_b) / 1e12, unit="TFLOP/s (useful causal, fp64)", cores=cores,
+                kind="oracle", seconds=round(t_f + t_b, 2),
+                forward=dict(tflops=fl_f / t_f / 1e12, seconds=round(t_f, 2), n_seq=S_f),
+                backward=dict(tflops=fl_b / t_b / 1e12, seconds=round(t_b, 2), n_seq=S_b),
+                sample="1 head, d=128: oracle.causal_attention at S=%d (%.1f GFLOP useful) and "
+                       "oracle.causal_attention_grad at S=%d (%.1f GFLOP useful)" %
+                       (S_f, fl_f / 1e9, S_b, fl_b / 1e9))
 
 
-def traffic_fields(workload, name):
-    t = TRAFFIC.get(workload, {}).get(name)
-    if t is None:
-        return dict(traffic=None)
-    # bytes per launch (read + written), with the split and the algorithmic figure beside it
-    return dict(traffic=int(round((t["read_GB"] + t["written_GB"]) * 1e9)), traffic_detail=t)
+def device_info():
+    """Compute units and clock as the runtime reports them, and the bf16 MFMA peak they imply
+    (4096 flop per clock and compute unit); the roofline keeps the published 2.5 PFLOP/s."""
+    p = torch.cuda.get_device_properties(0)
+    cus = int(p.multi_processor_count)
+    khz = getattr(p, "clock_rate", None)
+    info = {"name": p.name, "compute_units": cus, "max_clock_mhz": None if not khz else round(khz / 1e3, 1),
+            "hbm_GB": round(p.total_memory / 1e9, 1)}
+    if khz:
+        info["bf16_peak_from_cus_and_clock_tflops"] = round(cus * khz * 1e3 * 4096 / 1e12, 1)
+    return info
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=None,
+                    help="timed passes (default 10; 50 for the workloads whose steps last under 1 ms)")
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg3", choices=sorted(WORKLOADS))
     ap.add_argument("--bwd", type=int, default=1, help="0: forward ring only (default: forward + backward)")
@@ -264,6 +298,8 @@ def main():
         sys.exit(1)
     sa.lib()
     w = dict(WORKLOADS[args.workload])
+    if args.steps is None:
+        args.steps = 50 if args.workload in ("cfg2", "tiny") else 10
     if args.kv_heads:
         if args.kv_heads < 1 or w["H"] % args.kv_heads:
             ap.error("--kv-heads must divide the workload's %d heads" % w["H"])
@@ -288,10 +324,11 @@ def main():
     N = w["N"]
     avg = lambda tabs: [[sum(t[i][j] for t in tabs) / len(tabs) for j in range(N)] for i in range(N)]
     low = lambda tabs: [[min(t[i][j] for t in tabs) for j in range(N)] for i in range(N)]
+    med = lambda tabs: [[statistics.median(t[i][j] for t in tabs) for j in range(N)] for i in range(N)]
     per_pair_total = 4 + (10 if args.bwd else 0)
     flops = useful_flops(w, sa.STRIPED, per_pair_total)
     value = flops / (ms_per_step * 1e9)
-    striped_rows, striped_worst = summarize_steps(w, sa.STRIPED, avg(tables_f), 4, low(tables_f))
+    striped_rows, striped_worst = summarize_steps(w, sa.STRIPED, avg(tables_f), 4, low(tables_f), med(tables_f))
 
     # the comparison layout, same shapes (not part of `value`)
     run.one_pass(sa.CONTIGUOUS, False)
@@ -301,22 +338,39 @@ def main():
         tf, tb = run.one_pass(sa.CONTIGUOUS, True)
         ctab_f.append(tf)
         ctab_b.append(tb)
-    contig_rows, contig_worst = summarize_steps(w, sa.CONTIGUOUS, avg(ctab_f), 4, low(ctab_f))
+    contig_rows, contig_worst = summarize_steps(w, sa.CONTIGUOUS, avg(ctab_f), 4, low(ctab_f), med(ctab_f))
 
     # roofline per kernel family: algorithmic flops of one launch / its average HIP-event
     # duration (events recorded by the ring driver on the launch stream); the dominant one
     # (largest share of the pass) is reported as "roofline"
-    def roof(rows, name):
+    plain = not args.kv_heads and skip == (0, 0)
+    traffic = measured_traffic(args.workload) if plain else {}
+    c_rows = w["S"] // N
+
+    def roof(rows, family, alg_bytes):
+        name, kernels = FAMILIES[family]
         live = [r for r in rows if r["ms"] > 0]
         tot_ms = sum(r["ms"] for r in live)
         ach = sum(r["tflops"] * r["ms"] for r in live) / max(1e-9, tot_ms)
-        return dict(bound="mfma", kernel=name, achieved=round(ach, 1), peak=PEAK_BF16_TFLOPS,
-                    unit="TFLOP/s", frac=round(ach / PEAK_BF16_TFLOPS, 4), **traffic_fields("" if args.kv_heads else args.workload, name),
-                    avg_launch_ms=round(tot_ms / max(1, len(live)), 4), total_ms=round(tot_ms, 3))
-    roofs = {"fwd": roof(striped_rows, "fwd ring step (fwd_mfma_kernel)")}
+        out = dict(bound="mfma", kernel=name, achieved=round(ach, 1), peak=PEAK_BF16_TFLOPS,
+                   unit="TFLOP/s", frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=None,
+                   avg_launch_ms=round(tot_ms / max(1, len(live)), 4), total_ms=round(tot_ms, 3))
+        if all(k in traffic for k in kernels):      # bytes per launch (read + written) from the profile
+            rd, wr = (sum(traffic[k][i] for k in kernels) for i in (0, 1))
+            out["traffic"] = int(round((rd + wr) * 1e9))
+            out["traffic_detail"] = {"read_GB": round(rd, 2), "written_GB": round(wr, 2),
+                                     "algorithmic_GB": round(alg_bytes / 1e9, 2),
+                                     "source": "profiles/ring_step_kernels_%s.txt" % args.workload}
+        return out
+    # algorithmic bytes of one step: Q, K, V once, O and LSE read and written (forward);
+    # Q, K, V, dO once per kernel, LSE and delta, dQ / dK / dV read and written (backward)
+    bh = w["B"] * w["H"]
+    alg_f = bh * c_rows * (3 * w["d"] * 2 + 2 * w["d"] * 4 + 2 * 4)
+    alg_b = bh * c_rows * (2 * 4 * w["d"] * 2 + 2 * 2 * 4 + 3 * 2 * w["d"] * 4)
+    roofs = {"fwd": roof(striped_rows, "fwd", alg_f)}
     if args.bwd:
         rows_b, _ = summarize_steps(w, sa.STRIPED, avg(tables_b), 10)
-        roofs["bwd"] = roof(rows_b, "bwd ring step (bwd_dq_mfma_kernel + bwd_dkdv_mfma_kernel)")
+        roofs["bwd"] = roof(rows_b, "bwd", alg_b)
     roofline = max(roofs.values(), key=lambda r: r["total_ms"])
 
     result = {
@@ -329,6 +383,7 @@ def main():
                    "n_seq": w["S"], "N": N, "c": w["S"] // N, "q_dev": w["q_dev"],
                    "pass": "stripe_permute + ring fwd" + (" + ring bwd" if args.bwd else "") + " + finalize"},
         "frac_of_bf16_peak": round(value / PEAK_BF16_TFLOPS, 4),
+        "device": device_info(),
         "roofline": roofline,
         "roofline_by_kernel": roofs,
         "striped": {"worst_device_ms_per_round": striped_worst, "ring_sum_ms": round(sum(striped_worst), 4),
@@ -341,9 +396,9 @@ def main():
                          "not step latencies",
     }
     if args.bwd:
-        rb, wb = summarize_steps(w, sa.STRIPED, avg(tables_b), 10, low(tables_b))
+        rb, wb = summarize_steps(w, sa.STRIPED, avg(tables_b), 10, low(tables_b), med(tables_b))
         result["striped"]["bwd_steps"], result["striped"]["bwd_worst_device_ms_per_round"] = rb, wb
-        rb, wb = summarize_steps(w, sa.CONTIGUOUS, avg(ctab_b), 10, low(ctab_b))
+        rb, wb = summarize_steps(w, sa.CONTIGUOUS, avg(ctab_b), 10, low(ctab_b), med(ctab_b))
         result["contiguous"]["bwd_steps"], result["contiguous"]["bwd_worst_device_ms_per_round"] = rb, wb
     if skip != (0, 0):
         from paper_2311_09431_amd import tms

@@ -16,8 +16,13 @@
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    Calls only enqueue work; they do not synchronise, except sa_ring_fwd /
  *    sa_ring_bwd when asked for per-step timings.
- *  - Return value: SA_OK (0) or a negative sa_status.  On any error nothing
- *    has been launched.  No entry point throws.
+ *  - Return value: SA_OK (0) or a negative sa_status.  Arguments are validated
+ *    before anything is enqueued: on every error except SA_ERR_HIP nothing has
+ *    been launched.  SA_ERR_HIP from a single-kernel entry point means its launch
+ *    failed; from the ring drivers (and from a backward step, which is several
+ *    launches) it can come after earlier kernels were enqueued, and the read-
+ *    modify-write outputs (O, LSE, dQ, dK, dV) are then undefined.  No entry
+ *    point throws.
  *  - Pointers must be aligned to 16 bytes (permutes: to min(16, inner_bytes
  *    rounded down to a power of two)).
  *  - Notation follows the paper: N devices, block size c = n_seq / N, query
@@ -52,8 +57,11 @@ typedef struct {
     int32_t c;             /* rows per device (block size) */
     int32_t d;             /* head dimension: any multiple of 4 up to 256 (Table 1's
                               models have 128 and 100);
-                              bf16 with d <= 128 and c >= 128 takes the MFMA kernels
-                              (d < 128 zero-padded to 128 columns) */
+                              bf16 with d <= 128 and c >= 128 takes the MFMA kernels, which
+                              compute 64 columns for d <= 64 and 128 otherwise; the
+                              columns beyond d are zeros on both sides of every product:
+                              nothing that follows a row's d elements in memory is read
+                              into a result, and nothing beyond them is written) */
     int64_t stride_b;      /* elements between batches in Q/K/V/dO/O/dQ/dK/dV */
     int64_t stride_h;      /* elements between heads in the same tensors */
     int64_t stride_s;      /* elements between consecutive rows; 0 selects d.  A multiple of 4,
@@ -215,8 +223,10 @@ int sa_ring_bwd_tiled(const void* Q, const void* K, const void* V, const void* d
 
 /*
  * Host-only helpers (no GPU work).
- * sa_mask_offset: the step's mask as "allowed iff b <= a - off": returns 0 and
- * writes *off (0 or 1), or writes *kind = 0 empty / 1 triangular / 2 full.
+ * sa_step_mask: the step's mask, GetMask(q_dev, kv_dev) of Sec. 2.2 / 2.3 in local
+ * indices.  Writes both outputs: *kind = 0 empty (nothing allowed) / 1 triangular (key b
+ * allowed for query a iff b <= a - *off) / 2 full (everything allowed), and *off = 0 or 1
+ * (0 unless the block is triangular).  Errors: NULL, DEV, LAYOUT.
  * sa_step_pairs: number of allowed (query, key) pairs of the step, i.e. Work(j, k)
  * of Sec. 2.3 for the striped layout and c^2 / c(c+1)/2 / 0 for the contiguous one.
  */

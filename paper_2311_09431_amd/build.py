@@ -57,22 +57,5 @@ def build_library(extra_flags=(), jobs=8):
     return LIB
 
 
-def build_ubench():
-    """Compile the hardware-ceiling microbenchmark (csrc/ubench/mfma_ceiling.hip) to
-    _build/mfma_ceiling.  Not part of the library; run it on the GPU by hand."""
-    os.makedirs(OBJ_DIR, exist_ok=True)
-    exe = os.path.join(OBJ_DIR, "mfma_ceiling")
-    cmd = [_hipcc(), "-O3", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
-           "-packed-fp32-ops", "-Wno-unused-command-line-argument",
-           os.path.join(CSRC, "ubench", "mfma_ceiling.hip"), "-o", exe]
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode:
-        raise RuntimeError("hipcc failed on the microbenchmark:\n%s\n%s" % (r.stdout, r.stderr))
-    return exe
-
-
 if __name__ == "__main__":
-    if sys.argv[1:] == ["--ubench"]:
-        print(build_ubench())
-    else:
-        print(build_library(sys.argv[1:]))
+    print(build_library(sys.argv[1:]))

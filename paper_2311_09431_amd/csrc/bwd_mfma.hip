@@ -51,20 +51,28 @@ __device__ inline bf16x8 pack8(const f32x16& x, int first) {
 // Two barriers per 64-key tile: one makes the tile requested one iteration earlier
 // visible, one releases the tile just finished for the next request.
 
-template <bool NEXT, bool MASK>
+// DP: columns computed (128, or 64 for head dimensions up to 64: k-steps 4..7 of the S and dP
+// products and column blocks 2, 3 of the dQ product do not exist then).  PART: d % 8 == 4, the
+// K and V fragments that hold column d are cleared beyond it (part_ks = the k-step, or -1 for
+// the lanes of the other half-wave).
+template <bool NEXT, bool MASK, int DP, bool PART>
 __device__ inline void dq_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, f32x16& dp_next,
                                f32x16 (&acc)[4], const bf16x8 (&qf)[8], const bf16x8 (&gf)[8],
                                float kappa, float lse2, float delta, const uint32_t (&arow)[8],
                                const uint32_t (&tr0)[4], const uint32_t (&tr1)[4],
-                               const char* k_next, const char* v_next, const char* k_cur, int mask_lim) {
+                               const char* k_next, const char* v_next, const char* k_cur, int mask_lim,
+                               int part_ks) {
+    constexpr int KS = DP / 16, MB = DP / 32;
     bf16x8 ka[8], va[8], kt[8], dsb[2];
     auto fetch = [&](int i) {
-        if (NEXT) {
+        if (NEXT && i < KS) {
             ka[i] = dt_read_row(k_next, arow[i]);
             va[i] = dt_read_row(v_next, arow[i]);
         }
     };
-    auto fetch_t = [&](int i) { kt[i] = dt_read_tr(k_cur + (i / 4) * 16 * 256, tr0[i % 4], tr1[i % 4]); };
+    auto fetch_t = [&](int i) {
+        if (i % 4 < MB) kt[i] = dt_read_tr(k_cur + (i / 4) * 16 * 256, tr0[i % 4], tr1[i % 4]);
+    };
     fetch(0);
     fetch(1);
     if (NEXT) {
@@ -76,9 +84,9 @@ __device__ inline void dq_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, f3
         __builtin_amdgcn_sched_barrier(0);          // slices stay in program order
         if (i + 2 < 8) fetch(i + 2);
         if (i >= 4) fetch_t(i - 4);                 // first half of the K^T operands
-        if (NEXT) {
-            s_next = mfma(ka[i], qf[i], s_next);
-            dp_next = mfma(va[i], gf[i], dp_next);
+        if (NEXT && i < KS) {
+            s_next = mfma(PART ? zero_beyond_d(ka[i], i == part_ks) : ka[i], qf[i], s_next);
+            dp_next = mfma(PART ? zero_beyond_d(va[i], i == part_ks) : va[i], gf[i], dp_next);
         }
 #pragma unroll
         for (int r = 2 * i; r < 2 * i + 2; ++r) {
@@ -91,7 +99,7 @@ __device__ inline void dq_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, f3
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         if (i + 4 < 8) fetch_t(i + 4);
-        acc[i % 4] = mfma(kt[i], dsb[i / 4], acc[i % 4]);
+        if (i % 4 < MB) acc[i % 4] = mfma(kt[i], dsb[i / 4], acc[i % 4]);
         __builtin_amdgcn_sched_barrier(0);
     }
 }
@@ -103,9 +111,10 @@ __device__ inline void dq_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, f3
 // and are removed by the mask.
 // (FULL is a template argument rather than a launch argument so that profiler traces name
 // triangular and full launches apart; the code is the same.)
-template <bool RAGGED, bool FULL>
+template <bool RAGGED, bool FULL, int DP, bool PART>
 __global__ void __launch_bounds__(256, 2)
 bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
+    constexpr int KS = DP / 16, MB = DP / 32;
     // one LDS object per tile buffer
     __shared__ __attribute__((aligned(1024))) char k_lds0[DT_BYTES];
     __shared__ __attribute__((aligned(1024))) char k_lds1[DT_BYTES];
@@ -150,7 +159,7 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
     uint32_t arow[8], tr0[4], tr1[4], gl[4];
     dt_row_addrs(arow, n, h);
     dt_tr_addrs(tr0, tr1, lane);
-    dt_load_offsets(gl, lane, wave, pitch);
+    dt_load_offsets(gl, lane, wave, pitch, d);
     dt_load(Kr, 0, k_lds0, gl, wave);
     dt_load(Vr, 0, v_lds0, gl, wave);
     dt_load(Kr, tile_pitch, k_lds1, gl, wave);       // n_kt >= 2 always
@@ -174,14 +183,17 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
+    // PART: k-step whose fragment, in this half-wave, is the chunk holding column d
+    const int part_ks = (PART && ((d >> 3) & 1) == h) ? (d >> 4) : -1;
     f32x16 s_a, s_b, dp_a, dp_b;
     {   // prologue: S(0), dP(0)
 #pragma unroll
         for (int r = 0; r < 16; ++r) s_a[r] = dp_a[r] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            s_a = mfma(dt_read_row(k_lds0, arow[ks]), qf[ks], s_a);
-            dp_a = mfma(dt_read_row(v_lds0, arow[ks]), gf[ks], dp_a);
+        for (int ks = 0; ks < KS; ++ks) {
+            const bf16x8 ka = dt_read_row(k_lds0, arow[ks]), va = dt_read_row(v_lds0, arow[ks]);
+            s_a = mfma(PART ? zero_beyond_d(ka, ks == part_ks) : ka, qf[ks], s_a);
+            dp_a = mfma(PART ? zero_beyond_d(va, ks == part_ks) : va, gf[ks], dp_a);
         }
     }
 
@@ -194,14 +206,15 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
         char* const v_cur = PAR ? v_lds1 : v_lds0;
         char* const k_nxt = PAR ? k_lds0 : k_lds1;
         char* const v_nxt = PAR ? v_lds0 : v_lds1;
-        dq_step<true, MASK>(s_a, dp_a, s_b, dp_b, acc, qf, gf, kappa, lse2, delta, arow, tr0, tr1,
-                            k_cur + DT_BYTES / 2, v_cur + DT_BYTES / 2, k_cur, mask_base - 64 * t);
+        dq_step<true, MASK, DP, PART>(s_a, dp_a, s_b, dp_b, acc, qf, gf, kappa, lse2, delta, arow, tr0, tr1,
+                                      k_cur + DT_BYTES / 2, v_cur + DT_BYTES / 2, k_cur, mask_base - 64 * t,
+                                      part_ks);
         if (!LAST) {
             __builtin_amdgcn_s_waitcnt(0);      // tile t+1, requested one iteration ago, has landed
             __syncthreads();
         }
-        dq_step<!LAST, MASK>(s_b, dp_b, s_a, dp_a, acc, qf, gf, kappa, lse2, delta, arow, tr0, tr1,
-                             k_nxt, v_nxt, k_cur + DT_BYTES / 2, mask_base - 64 * t - 32);
+        dq_step<!LAST, MASK, DP, PART>(s_b, dp_b, s_a, dp_a, acc, qf, gf, kappa, lse2, delta, arow, tr0, tr1,
+                                       k_nxt, v_nxt, k_cur + DT_BYTES / 2, mask_base - 64 * t - 32, part_ks);
         if (!LAST) {
             __syncthreads();                    // every wavefront is done with tile t
             if (t + 2 < n_kt) {
@@ -229,7 +242,7 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
     trip(T{}, T{}, P1{}, t + 1);
 
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
+    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             const int col = 32 * mb + 8 * g + 4 * h;
@@ -246,9 +259,20 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
 // MFMA whose accumulator is pinned to ordinary VGPRs.  The dK/dV kernel needs more than 256
 // registers, and once a kernel uses AGPRs the compiler places EVERY MFMA result there; the
 // S / dP tiles are consumed by VALU instructions, so they would be copied back register by
-// register.  Results of these are read by VALU code one whole pipeline step later (hundreds
-// of cycles), far beyond the MFMA -> VALU read hazard window the compiler cannot see through
-// the asm; the prologue, where the distance is short, waits explicitly.
+// register.
+//
+// Issued from inline assembly, these MFMAs are invisible to the compiler's hazard recogniser,
+// so the one software-managed hazard they have is kept by hand.  ISA guide, "Manually inserted
+// wait states (NOPs)": XDL (matrix core) write of a VGPR followed by a VALU read or write of
+// it needs passes + 3 wait states: 11 for this 8-pass instruction (19 for a 16-pass one).
+//  * In the loops the distance is structural: the last S / dP MFMA of a pipeline step is
+//    followed by that step's dV / dK products, 4 * MB >= 8 further MFMAs of 8 passes each
+//    (>= 256 cycles of the same in-order pipeline), before the next step's first VALU read.
+//  * In the prologue nothing lies between: mfma_results_to_valu() inserts 32 wait states and
+//    ties the two tiles to the asm statement, so no read of them can be scheduled before it.
+__device__ inline void mfma_results_to_valu(f32x16& a, f32x16& b) {
+    asm volatile("s_nop 15\n\ts_nop 15" : "+v"(a), "+v"(b));
+}
 __device__ inline void mfma_vgpr_first(f32x16& acc, bf16x8 a, bf16x8 b) {
     asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "v"(b));
 }
@@ -278,24 +302,28 @@ __device__ inline void load_neg_delta(f32x16& dp, const float* neg_delta, int h)
     }
 }
 
-template <bool NEXT, bool MASK>
+template <bool NEXT, bool MASK, int DP, bool PART>
 __device__ inline void dkdv_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, f32x16& dp_next,
                                  f32x16 (&acck)[4], f32x16 (&accv)[4], const bf16x8 (&kf)[8],
                                  const bf16x8 (&vf)[8], float kappa, const uint32_t (&arow)[8],
                                  const uint32_t (&tr0)[4], const uint32_t (&tr1)[4], const char* q_next,
                                  const char* g_next, const char* q_cur, const char* g_cur,
-                                 const float* stat_cur, const float* stat_next, int h, int mask_lim) {
+                                 const float* stat_cur, const float* stat_next, int h, int mask_lim,
+                                 int part_ks) {
+    constexpr int KS = DP / 16, MB = DP / 32;
     bf16x8 qa[8], ga[8], qt[8], gt[8], pb[2], dsb[2];
     if (NEXT) load_neg_delta(dp_next, stat_next + DT_ROWS, h);
     auto fetch = [&](int i) {
-        if (NEXT) {
+        if (NEXT && i < KS) {
             qa[i] = dt_read_row(q_next, arow[i]);
             ga[i] = dt_read_row(g_next, arow[i]);
         }
     };
     auto fetch_t = [&](int i) {
-        gt[i] = dt_read_tr(g_cur + (i / 4) * 16 * 256, tr0[i % 4], tr1[i % 4]);
-        qt[i] = dt_read_tr(q_cur + (i / 4) * 16 * 256, tr0[i % 4], tr1[i % 4]);
+        if (i % 4 < MB) {
+            gt[i] = dt_read_tr(g_cur + (i / 4) * 16 * 256, tr0[i % 4], tr1[i % 4]);
+            qt[i] = dt_read_tr(q_cur + (i / 4) * 16 * 256, tr0[i % 4], tr1[i % 4]);
+        }
     };
     // LSE * log2(e) of this lane's query rows 8 (r/4) + 4h + r%4, two per slice
     float2 lv[8];
@@ -316,10 +344,12 @@ __device__ inline void dkdv_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, 
             fetch_stat(i + AHEAD);
         }
         if (i >= 5) fetch_t(i - 5);                 // transposed operands 0..2 ahead of their use
-        if (NEXT) {
-            if (i == 0) mfma_vgpr_first(s_next, qa[0], kf[0]);
-            else mfma_vgpr_acc(s_next, qa[i], kf[i]);
-            mfma_vgpr_acc(dp_next, ga[i], vf[i]);
+        if (NEXT && i < KS) {
+            const bf16x8 qx = PART ? zero_beyond_d(qa[i], i == part_ks) : qa[i];
+            const bf16x8 gx = PART ? zero_beyond_d(ga[i], i == part_ks) : ga[i];
+            if (i == 0) mfma_vgpr_first(s_next, qx, kf[0]);
+            else mfma_vgpr_acc(s_next, qx, kf[i]);
+            mfma_vgpr_acc(dp_next, gx, vf[i]);
         }
 #pragma unroll
         for (int r = 2 * i; r < 2 * i + 2; ++r) {
@@ -334,8 +364,10 @@ __device__ inline void dkdv_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, 
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         if (i + 3 < 8) fetch_t(i + 3);
-        accv[i % 4] = mfma(gt[i], pb[i / 4], accv[i % 4]);
-        acck[i % 4] = mfma(qt[i], dsb[i / 4], acck[i % 4]);
+        if (i % 4 < MB) {
+            accv[i % 4] = mfma(gt[i], pb[i / 4], accv[i % 4]);
+            acck[i % 4] = mfma(qt[i], dsb[i / 4], acck[i % 4]);
+        }
         __builtin_amdgcn_sched_barrier(0);
     }
 }
@@ -343,9 +375,10 @@ __device__ inline void dkdv_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, 
 // RAGGED (c not a multiple of 128): key rows beyond the shard are loaded from its last row and
 // not stored; query rows beyond it come in as zero rows of Q and dO with LSE = +inf, so their
 // P and dS are exactly zero.
-template <bool TRI, bool RAGGED = false>
+template <bool TRI, bool RAGGED, int DP, bool PART>
 __global__ void __launch_bounds__(256, 1)
 bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
+    constexpr int KS = DP / 16, MB = DP / 32;
     // one LDS object per tile buffer
     __shared__ __attribute__((aligned(1024))) char q_lds0[DT_BYTES];
     __shared__ __attribute__((aligned(1024))) char q_lds1[DT_BYTES];
@@ -395,7 +428,7 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
     uint32_t arow[8], tr0[4], tr1[4], gl[4];
     dt_row_addrs(arow, n, h);
     dt_tr_addrs(tr0, tr1, lane);
-    dt_load_offsets(gl, lane, wave, pitch);
+    dt_load_offsets(gl, lane, wave, pitch, d);
     // t_first and n_qt are even (k0 and c are multiples of 128): tile t_first goes to buffer 0
     // and there are always at least two tiles
     dt_load(Qr, t_first * tile_pitch, q_lds0, gl, wave);
@@ -439,19 +472,25 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
+    // PART: k-step whose fragment, in this half-wave, is the chunk holding column d
+    const int part_ks = (PART && ((d >> 3) & 1) == h) ? (d >> 4) : -1;
     f32x16 s_a, s_b, dp_a, dp_b;
     {   // prologue: S, dP of the first sub-tile
         const char* q0p = q_lds0;
         const char* g0p = g_lds0;
         load_neg_delta(dp_a, stat + DT_ROWS, h);          // tile t_first is in buffer 0
-        mfma_vgpr_first(s_a, dt_read_row(q0p, arow[0]), kf[0]);
-        mfma_vgpr_acc(dp_a, dt_read_row(g0p, arow[0]), vf[0]);
 #pragma unroll
-        for (int ks = 1; ks < 8; ++ks) {
-            mfma_vgpr_acc(s_a, dt_read_row(q0p, arow[ks]), kf[ks]);
-            mfma_vgpr_acc(dp_a, dt_read_row(g0p, arow[ks]), vf[ks]);
+        for (int ks = 0; ks < KS; ++ks) {
+            bf16x8 qx = dt_read_row(q0p, arow[ks]), gx = dt_read_row(g0p, arow[ks]);
+            if (PART) {
+                qx = zero_beyond_d(qx, ks == part_ks);
+                gx = zero_beyond_d(gx, ks == part_ks);
+            }
+            if (ks == 0) mfma_vgpr_first(s_a, qx, kf[0]);
+            else mfma_vgpr_acc(s_a, qx, kf[ks]);
+            mfma_vgpr_acc(dp_a, gx, vf[ks]);
         }
-        __builtin_amdgcn_s_sleep(2);      // let the last two MFMAs retire before VALU code reads them
+        mfma_results_to_valu(s_a, dp_a);
     }
 
     float rstat = 0.f;          // statistics of the tile after next, in flight
@@ -465,16 +504,16 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
         char* const g_nxt = PAR ? g_lds0 : g_lds1;
         const float* st = stat + PAR * 2 * DT_ROWS;
         const float* st_nxt = stat + (1 - PAR) * 2 * DT_ROWS;       // statistics of tile t + 1
-        dkdv_step<true, MASK>(s_a, dp_a, s_b, dp_b, acck, accv, kf, vf, kappa, arow, tr0, tr1,
+        dkdv_step<true, MASK, DP, PART>(s_a, dp_a, s_b, dp_b, acck, accv, kf, vf, kappa, arow, tr0, tr1,
                               q_cur + DT_BYTES / 2, g_cur + DT_BYTES / 2, q_cur, g_cur, st, st + 32, h,
-                              mask_base - 64 * t);
+                              mask_base - 64 * t, part_ks);
         if (!last) {
             if (t > t_first) stat_store(t + 1, rstat);     // fetched at the end of trip t-1
             __builtin_amdgcn_s_waitcnt(0);       // tile t+1, requested one iteration ago, has landed
             __syncthreads();
-            dkdv_step<true, MASK>(s_b, dp_b, s_a, dp_a, acck, accv, kf, vf, kappa, arow, tr0, tr1, q_nxt,
+            dkdv_step<true, MASK, DP, PART>(s_b, dp_b, s_a, dp_a, acck, accv, kf, vf, kappa, arow, tr0, tr1, q_nxt,
                                   g_nxt, q_cur + DT_BYTES / 2, g_cur + DT_BYTES / 2, st + 32, st_nxt, h,
-                                  mask_base - 64 * t - 32);
+                                  mask_base - 64 * t - 32, part_ks);
             __syncthreads();                     // every wavefront is done with tile t
             if (t + 2 < n_qt) {
                 dt_load(Qr, (t + 2) * tile_pitch, q_cur, gl, wave);
@@ -482,9 +521,9 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
                 rstat = stat_fetch();
             }
         } else {
-            dkdv_step<false, MASK>(s_b, dp_b, s_a, dp_a, acck, accv, kf, vf, kappa, arow, tr0, tr1, q_nxt,
+            dkdv_step<false, MASK, DP, PART>(s_b, dp_b, s_a, dp_a, acck, accv, kf, vf, kappa, arow, tr0, tr1, q_nxt,
                                    g_nxt, q_cur + DT_BYTES / 2, g_cur + DT_BYTES / 2, st + 32, st_nxt, h,
-                                   mask_base - 64 * t - 32);
+                                   mask_base - 64 * t - 32, part_ks);
         }
     };
     using T = std::true_type;
@@ -513,7 +552,7 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
     }
 
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
+    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             const int col = 32 * mb + 8 * g + 4 * h;
@@ -538,21 +577,25 @@ bool bwd_mfma_supported(const StepArgs& a, int dtype) {
     // its first
     const int64_t widest = a.stride_s > a.kv_stride_s ? a.stride_s : a.kv_stride_s;
     const int64_t rows = (int64_t)(a.c + BM - 1) / BM * BM;
+    // one workgroup per (128-row tile, batch, head) in a 1-D grid
+    if (rows / BM * a.B * a.H >= (int64_t(1) << 31)) return false;
     return dtype == SA_BF16 && a.d <= D && a.d % 4 == 0 && a.c >= BM &&
            rows * 2 * widest + 2 * a.d < (int64_t(1) << 31);
 }
 
-hipError_t launch_bwd_mfma(const StepArgs& a, hipStream_t st) {
+namespace {
+template <int DP, bool PART>
+hipError_t launch_bwd_variant(const StepArgs& a, hipStream_t st) {
     const int n_tiles = (a.c + BM - 1) / BM;
     const bool ragged = a.c % BM != 0;
-    const dim3 grid_q(n_tiles * a.B * a.H), grid_kv(n_tiles * a.B * a.H_kv), block(256);
+    const dim3 grid_q((unsigned)n_tiles * a.B * a.H), grid_kv((unsigned)n_tiles * a.B * a.H_kv), block(256);
     const bool full = a.kind == MASK_FULL;
     if (ragged) {
-        if (full) hipLaunchKernelGGL((bwd_dq_mfma_kernel<true, true>), grid_q, block, 0, st, a, n_tiles);
-        else hipLaunchKernelGGL((bwd_dq_mfma_kernel<true, false>), grid_q, block, 0, st, a, n_tiles);
+        if (full) hipLaunchKernelGGL((bwd_dq_mfma_kernel<true, true, DP, PART>), grid_q, block, 0, st, a, n_tiles);
+        else hipLaunchKernelGGL((bwd_dq_mfma_kernel<true, false, DP, PART>), grid_q, block, 0, st, a, n_tiles);
     } else {
-        if (full) hipLaunchKernelGGL((bwd_dq_mfma_kernel<false, true>), grid_q, block, 0, st, a, n_tiles);
-        else hipLaunchKernelGGL((bwd_dq_mfma_kernel<false, false>), grid_q, block, 0, st, a, n_tiles);
+        if (full) hipLaunchKernelGGL((bwd_dq_mfma_kernel<false, true, DP, PART>), grid_q, block, 0, st, a, n_tiles);
+        else hipLaunchKernelGGL((bwd_dq_mfma_kernel<false, false, DP, PART>), grid_q, block, 0, st, a, n_tiles);
     }
     hipError_t e = hipGetLastError();
     // dK, dV: the members of a group of query heads one after the other, each adding to the
@@ -560,15 +603,22 @@ hipError_t launch_bwd_mfma(const StepArgs& a, hipStream_t st) {
     StepArgs m = a;
     for (m.member = 0; m.member < a.H / a.H_kv && e == hipSuccess; ++m.member) {
         if (a.kind == MASK_TRI) {
-            if (ragged) hipLaunchKernelGGL((bwd_dkdv_mfma_kernel<true, true>), grid_kv, block, 0, st, m, n_tiles);
-            else hipLaunchKernelGGL((bwd_dkdv_mfma_kernel<true>), grid_kv, block, 0, st, m, n_tiles);
+            if (ragged) hipLaunchKernelGGL((bwd_dkdv_mfma_kernel<true, true, DP, PART>), grid_kv, block, 0, st, m, n_tiles);
+            else hipLaunchKernelGGL((bwd_dkdv_mfma_kernel<true, false, DP, PART>), grid_kv, block, 0, st, m, n_tiles);
         } else {
-            if (ragged) hipLaunchKernelGGL((bwd_dkdv_mfma_kernel<false, true>), grid_kv, block, 0, st, m, n_tiles);
-            else hipLaunchKernelGGL((bwd_dkdv_mfma_kernel<false>), grid_kv, block, 0, st, m, n_tiles);
+            if (ragged) hipLaunchKernelGGL((bwd_dkdv_mfma_kernel<false, true, DP, PART>), grid_kv, block, 0, st, m, n_tiles);
+            else hipLaunchKernelGGL((bwd_dkdv_mfma_kernel<false, false, DP, PART>), grid_kv, block, 0, st, m, n_tiles);
         }
         e = hipGetLastError();
     }
     return e;
+}
+}  // namespace
+
+hipError_t launch_bwd_mfma(const StepArgs& a, hipStream_t st) {
+    const bool part = a.d % 8 != 0;
+    if (a.d <= 64) return part ? launch_bwd_variant<64, true>(a, st) : launch_bwd_variant<64, false>(a, st);
+    return part ? launch_bwd_variant<128, true>(a, st) : launch_bwd_variant<128, false>(a, st);
 }
 
 }  // namespace sa

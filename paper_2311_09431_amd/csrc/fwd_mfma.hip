@@ -112,18 +112,23 @@ __device__ inline bf16x8 lds_read_tr(const char* lds, uint32_t addr) {
 //   PV: oacc += V(u-1)^T p_prev        v_prev = LDS address of the 32 V rows of sub-tile u-1
 // MASK applies the element mask to s_cur: register r (key 8 (r/4) + 4h + r%4 of the
 // sub-tile) is allowed iff 8 (r/4) + r%4 <= mask_lim (mask_lim already holds -4h).
-template <bool QK, bool SM, bool PV, bool MASK>
+// DP: columns computed (128, or 64 for head dimensions up to 64: k-steps 4..7 of the first
+// product and column blocks 2, 3 of the second do not exist then).  PART: d % 8 == 4, the
+// K fragment that holds column d is cleared beyond it (part_ks = its k-step, or -1 for the
+// lanes of the other half-wave).
+template <bool QK, bool SM, bool PV, bool MASK, int DP, bool PART>
 __device__ inline void step(f32x16& s_cur, f32x16& s_next, bf16x8 (&p_cur)[2], bf16x8 (&p_prev)[2],
                             f32x16 (&oacc)[4], const bf16x8 (&qf)[8], float& m, float& l, float kappa,
                             const uint32_t (&kaddr)[4], const uint32_t (&vaddr)[4], const char* k_next,
-                            const char* v_prev, int mask_lim) {
+                            const char* v_prev, int mask_lim, int part_ks) {
+    constexpr int KS = DP / 16, MB = DP / 32;
     // Operands of slice i are requested from LDS two slices ahead, so only a few of
     // them are live at a time; slice i holds QK MFMA i (k-step i) and PV MFMA i
     // (16-key group i / 4, 32-column block i % 4).
     bf16x8 ka[8], va[8];
     auto fetch = [&](int i) {
-        if (QK) ka[i] = lds_read_b128(k_next, k_step_addr(kaddr, i));
-        if (PV) va[i] = lds_read_tr(v_prev + (i / 4) * 16 * 256, vaddr[i % 4]);
+        if (QK && i < KS) ka[i] = lds_read_b128(k_next, k_step_addr(kaddr, i));
+        if (PV && i % 4 < MB) va[i] = lds_read_tr(v_prev + (i / 4) * 16 * 256, vaddr[i % 4]);
     };
     fetch(0);
     fetch(1);
@@ -141,8 +146,8 @@ __device__ inline void step(f32x16& s_cur, f32x16& s_next, bf16x8 (&p_cur)[2], b
     for (int i = 0; i < 8; ++i) {
         __builtin_amdgcn_sched_barrier(0);         // slices stay in program order
         if (i + 2 < 8) fetch(i + 2);
-        if (QK) s_next = mfma(ka[i], qf[i], s_next);
-        if (PV) oacc[i % 4] = mfma(va[i], p_prev[i / 4], oacc[i % 4]);
+        if (QK && i < KS) s_next = mfma(PART ? zero_beyond_d(ka[i], i == part_ks) : ka[i], qf[i], s_next);
+        if (PV && i % 4 < MB) oacc[i % 4] = mfma(va[i], p_prev[i / 4], oacc[i % 4]);
         if (SM) {
             const float p0 = __builtin_amdgcn_exp2f(fmaf(s_cur[2 * i], kappa, -m));
             const float p1 = __builtin_amdgcn_exp2f(fmaf(s_cur[2 * i + 1], kappa, -m));
@@ -172,7 +177,7 @@ __device__ inline void step(f32x16& s_cur, f32x16& s_next, bf16x8 (&p_cur)[2], b
             m = m_new;
             l *= alpha;
 #pragma unroll
-            for (int mb = 0; mb < 4; ++mb)
+            for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) oacc[mb][r] *= alpha;
             rs = 0.f;
@@ -197,9 +202,10 @@ __device__ inline void step(f32x16& s_cur, f32x16& s_next, bf16x8 (&p_cur)[2], b
 // them).
 // (FULL is a template argument rather than a launch argument so that profiler traces name
 // triangular and full launches apart; the code is the same.)
-template <bool RAGGED, bool FULL>
+template <bool RAGGED, bool FULL, int DP, bool PART>
 __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1)
 fwd_mfma_kernel(StepArgs p, int n_qtiles) {
+    constexpr int KS = DP / 16, MB = DP / 32;
     // one LDS object per tile buffer
     __shared__ __attribute__((aligned(1024))) char k_lds0[TILE_BYTES];
     __shared__ __attribute__((aligned(1024))) char k_lds1[TILE_BYTES];
@@ -263,6 +269,9 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
         // V's swizzle depends on the row within the 4-row group only, so its four pieces
         // differ by exactly four rows: one lane offset, the rest goes into the scalar offset
         vg0 = (4 * LPW * wave + lr) * pitch + ((pc ^ (lr << 2)) << 4);
+        // chunks that start at or beyond column d are not fetched: their LDS columns get zeros
+        if (8 * (pc ^ (4 * wave + lr)) >= d) kg0 = DT_OUT_OF_RANGE;
+        if (8 * (pc ^ (lr << 2)) >= d) vg0 = DT_OUT_OF_RANGE;
     }
 
     // first tiles on their way while the running state is loaded
@@ -277,7 +286,7 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     float l = (h == 0) ? 1.f : 0.f;           // the two half-waves hold partial row sums
     f32x16 oacc[4];
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
+    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             const int col = 32 * mb + 8 * g + 4 * h;
@@ -290,6 +299,8 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     __builtin_amdgcn_s_waitcnt(0);     // the direct loads have landed (vmcnt) ...
     __syncthreads();                   // ... for every wavefront
 
+    // PART: k-step whose fragment, in this half-wave, is the chunk holding column d
+    const int part_ks = (PART && ((d >> 3) & 1) == h) ? (d >> 4) : -1;
     f32x16 s_a, s_b;
     bf16x8 p_a[2], p_b[2];
 #pragma unroll
@@ -301,7 +312,10 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) s_a[r] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) s_a = mfma(lds_read_b128(k_lds0, k_step_addr(kaddr, ks)), qf[ks], s_a);
+        for (int ks = 0; ks < KS; ++ks) {
+            const bf16x8 ka = lds_read_b128(k_lds0, k_step_addr(kaddr, ks));
+            s_a = mfma(PART ? zero_beyond_d(ka, ks == part_ks) : ka, qf[ks], s_a);
+        }
     }
 
     // Trip t = iterations u = 2t and 2t+1 with barrier t between them.  Iteration u does
@@ -321,14 +335,15 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
         char* const k_nxt = PAR ? k_lds0 : k_lds1;
         char* const v_cur = PAR ? v_lds1 : v_lds0;
         char* const v_prv = PAR ? v_lds0 : v_lds1;
-        step<true, true, !FIRST, MASK>(s_a, s_b, p_a, p_b, oacc, qf, m, l, kappa, kaddr, vaddr,
-                                       k_cur + TILE_BYTES / 2, v_prv + TILE_BYTES / 2, mask_base - 64 * t);
+        step<true, true, !FIRST, MASK, DP, PART>(s_a, s_b, p_a, p_b, oacc, qf, m, l, kappa, kaddr, vaddr,
+                                                 k_cur + TILE_BYTES / 2, v_prv + TILE_BYTES / 2,
+                                                 mask_base - 64 * t, part_ks);
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
         if (LD >= 2) load_tile_direct(K, (t + 2) * tile_pitch, k_cur, kg0, wave, pitch);
         if (LD >= 1) load_v_tile_direct(V, (t + 1) * tile_pitch, v_prv, vg0, wave, pitch);
-        step<!LAST, true, true, MASK>(s_b, s_a, p_b, p_a, oacc, qf, m, l, kappa, kaddr, vaddr, k_nxt, v_cur,
-                                      mask_base - 64 * t - 32);
+        step<!LAST, true, true, MASK, DP, PART>(s_b, s_a, p_b, p_a, oacc, qf, m, l, kappa, kaddr, vaddr, k_nxt,
+                                                v_cur, mask_base - 64 * t - 32, part_ks);
     };
     using T = std::true_type;
     using F = std::false_type;
@@ -369,14 +384,15 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     // final iteration u = 2 n_kt: PV(2 n_kt - 1): V tile n_kt - 1, second half; P in p_b
     {
         const char* v_last = v_lds1 + TILE_BYTES / 2;          // n_kt - 1 is odd
-        step<false, false, true, false>(s_a, s_b, p_a, p_b, oacc, qf, m, l, kappa, kaddr, vaddr, v_last, v_last, 0);
+        step<false, false, true, false, DP, PART>(s_a, s_b, p_a, p_b, oacc, qf, m, l, kappa, kaddr, vaddr, v_last,
+                                                  v_last, 0, part_ks);
     }
 
     // epilogue: normalise, store the merged state
     const float l_tot = half_wave_sum(l);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
+    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             float4 x;
@@ -395,20 +411,36 @@ bool fwd_mfma_supported(const StepArgs& a, int dtype) {
     // the last row of its last (possibly partial) tile pair must end below 2^31 bytes from
     // its first
     const int64_t rows = (int64_t)(a.c + BM - 1) / BM * BM;
+    // one workgroup per (128-row tile, batch, head) in a 1-D grid
+    if (rows / BM * a.B * a.H >= (int64_t(1) << 31)) return false;
     return dtype == SA_BF16 && a.d <= D && a.d % 4 == 0 && a.c >= BM &&
            rows * 2 * a.kv_stride_s + 2 * a.d < (int64_t(1) << 31);
 }
 
-hipError_t launch_fwd_mfma(const StepArgs& a, hipStream_t st) {
-    const int n_qtiles = (a.c + BM - 1) / BM;
-    const dim3 grid(n_qtiles * a.B * a.H), block(64 * NW);
+namespace {
+template <int DP, bool PART>
+void launch_fwd_variant(const StepArgs& a, hipStream_t st, dim3 grid, dim3 block, int n_qtiles) {
     const bool full = a.kind == MASK_FULL;
     if (a.c % BM) {
-        if (full) hipLaunchKernelGGL((fwd_mfma_kernel<true, true>), grid, block, 0, st, a, n_qtiles);
-        else hipLaunchKernelGGL((fwd_mfma_kernel<true, false>), grid, block, 0, st, a, n_qtiles);
+        if (full) hipLaunchKernelGGL((fwd_mfma_kernel<true, true, DP, PART>), grid, block, 0, st, a, n_qtiles);
+        else hipLaunchKernelGGL((fwd_mfma_kernel<true, false, DP, PART>), grid, block, 0, st, a, n_qtiles);
     } else {
-        if (full) hipLaunchKernelGGL((fwd_mfma_kernel<false, true>), grid, block, 0, st, a, n_qtiles);
-        else hipLaunchKernelGGL((fwd_mfma_kernel<false, false>), grid, block, 0, st, a, n_qtiles);
+        if (full) hipLaunchKernelGGL((fwd_mfma_kernel<false, true, DP, PART>), grid, block, 0, st, a, n_qtiles);
+        else hipLaunchKernelGGL((fwd_mfma_kernel<false, false, DP, PART>), grid, block, 0, st, a, n_qtiles);
+    }
+}
+}  // namespace
+
+hipError_t launch_fwd_mfma(const StepArgs& a, hipStream_t st) {
+    const int n_qtiles = (a.c + BM - 1) / BM;
+    const dim3 grid((unsigned)n_qtiles * a.B * a.H), block(64 * NW);
+    const bool part = a.d % 8 != 0;
+    if (a.d <= 64) {
+        if (part) launch_fwd_variant<64, true>(a, st, grid, block, n_qtiles);
+        else launch_fwd_variant<64, false>(a, st, grid, block, n_qtiles);
+    } else {
+        if (part) launch_fwd_variant<128, true>(a, st, grid, block, n_qtiles);
+        else launch_fwd_variant<128, false>(a, st, grid, block, n_qtiles);
     }
     return hipGetLastError();
 }

@@ -280,13 +280,12 @@ hipError_t launch_fwd_generic(const StepArgs& a, int dtype, hipStream_t st) {
 }
 
 hipError_t launch_bwd_generic(const StepArgs& a, int dtype, hipStream_t st) {
-    if (dtype == SA_F32) {
-        hipLaunchKernelGGL(bwd_dq_generic_kernel<float>, row_grid(a, a.H), dim3(kWaves * 64), 0, st, a);
-        hipLaunchKernelGGL(bwd_dkv_generic_kernel<float>, row_grid(a, a.H_kv), dim3(kWaves * 64), 0, st, a);
-    } else {
-        hipLaunchKernelGGL(bwd_dq_generic_kernel<__hip_bfloat16>, row_grid(a, a.H), dim3(kWaves * 64), 0, st, a);
-        hipLaunchKernelGGL(bwd_dkv_generic_kernel<__hip_bfloat16>, row_grid(a, a.H_kv), dim3(kWaves * 64), 0, st, a);
-    }
+    const dim3 block(kWaves * 64);
+    if (dtype == SA_F32) hipLaunchKernelGGL(bwd_dq_generic_kernel<float>, row_grid(a, a.H), block, 0, st, a);
+    else hipLaunchKernelGGL(bwd_dq_generic_kernel<__hip_bfloat16>, row_grid(a, a.H), block, 0, st, a);
+    if (hipError_t e = hipGetLastError()) return e;
+    if (dtype == SA_F32) hipLaunchKernelGGL(bwd_dkv_generic_kernel<float>, row_grid(a, a.H_kv), block, 0, st, a);
+    else hipLaunchKernelGGL(bwd_dkv_generic_kernel<__hip_bfloat16>, row_grid(a, a.H_kv), block, 0, st, a);
     return hipGetLastError();
 }
 

@@ -53,18 +53,34 @@ typedef __attribute__((address_space(3))) s16x4 lds_s16x4_t;
 
 __device__ inline int dt_swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
 
+// Head dimensions below 128.  A lane fetches the 16-byte chunk at logical position
+// pc ^ f(r) of its row.  A chunk that starts at or beyond column d is not fetched at all:
+// the lane's offset is set beyond the descriptor's range, for which the load is defined to
+// deliver zeros, so those LDS columns hold zeros whatever follows the row in memory.  When d
+// is not a multiple of 8 the last chunk of a row holds 4 valid columns and 4 columns of
+// whatever follows the row (the next row, a gap of the caller's layout); the kernels'
+// PART instantiations clear those four after reading the chunk from LDS (zero_beyond_d).
+constexpr uint32_t DT_OUT_OF_RANGE = 0x80000000u;     // >= any descriptor range (all are < 2^31)
+
 // byte offsets (within a tile, global side) of the 4 pieces this lane fetches
-// (pitch = bytes between rows in global memory, >= 2 d; a lane fetches 16 bytes at logical chunk
-// position pc ^ f(r) of its row whatever d is: past the row's end it picks up the following
-// rows, past the matrix's end zeros, and all of that lands in the padding columns >= d that
-// the other, zero-padded operand of every product cancels)
-__device__ inline void dt_load_offsets(uint32_t (&g)[4], int lane, int wave, int pitch) {
+// (pitch = bytes between rows in global memory, >= 2 d)
+__device__ inline void dt_load_offsets(uint32_t (&g)[4], int lane, int wave, int pitch, int d) {
     const int lr = lane >> 4, pc = lane & 15;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int r = 16 * wave + 4 * j + lr;
-        g[j] = r * pitch + ((pc ^ dt_swz(r)) << 4);
+        const int chunk = pc ^ dt_swz(r);
+        g[j] = 8 * chunk < d ? r * pitch + (chunk << 4) : DT_OUT_OF_RANGE;
     }
+}
+// PART (d % 8 == 4): fragment of k-step ks read by half h is the chunk 2 ks + h; in the chunk
+// that holds column d the elements 4..7 are beyond the row
+__device__ inline bf16x8 zero_beyond_d(bf16x8 x, bool is_last_chunk) {
+    typedef int i32x4 __attribute__((ext_vector_type(4)));
+    i32x4 v = __builtin_bit_cast(i32x4, x);
+    v[2] = is_last_chunk ? 0 : v[2];
+    v[3] = is_last_chunk ? 0 : v[3];
+    return __builtin_bit_cast(bf16x8, v);
 }
 // The loads go through a buffer descriptor held in scalar registers: the tile's byte
 // offset within the (batch, head) matrix is a scalar operand and the lane offset a 32-bit

@@ -35,3 +35,15 @@ def test_workloads_are_the_named_configurations():
     # useful work of the default pass: 8 triangular steps of c (c + 1) / 2 pairs, 14 d flops each
     c = 32768
     assert bench.useful_flops(w["cfg3"], 1, 14) == 8 * (c * (c + 1) // 2) * 32 * 14 * 128
+
+
+def test_traffic_comes_from_the_committed_profile_or_not_at_all():
+    sys.path.insert(0, ROOT)
+    import bench
+    t = bench.measured_traffic("cfg3")
+    # the summary of the default workload names all three matrix-core kernels
+    assert set(t) >= {"fwd_mfma_kernel", "bwd_dq_mfma_kernel", "bwd_dkdv_mfma_kernel"}
+    assert all(0 < rd < 100 and 0 < wr < 100 for rd, wr in t.values())
+    assert bench.measured_traffic("no-such-workload") == {}
+    for _, kernels in bench.FAMILIES.values():
+        assert all(k in t for k in kernels)

@@ -94,3 +94,48 @@ def test_rows_that_overlap_are_rejected():
         with pytest.raises(sa.StripedAttnError) as e:
             sa.sa_state_init(o.permute(0, 2, 1, 3), lse, bad)
         assert e.value.status in (-2, -6)
+
+
+@pytest.mark.parametrize("layout", [sa.CONTIGUOUS, sa.STRIPED])
+@pytest.mark.parametrize("d,pitch", [(100, 128), (64, 128), (36, 40), (124, 136)])
+def test_gap_between_rows_may_hold_anything(layout, d, pitch):
+    # Rows of d elements at a pitch of more than d, the gap filled with NaN (what an
+    # uninitialised buffer may hold): the matrix-core kernels compute 64 or 128 columns and
+    # must neither read the gap into a product nor write into it.
+    B, H, S, N = 1, 2, 768, 3
+    c = S // N
+    Q, K, V, dO = (x.cuda() for x in inputs.qkv(B, H, S, d, 900 + d, torch.bfloat16, with_dout=True))
+
+    def padded(x, dtype, fill):
+        store = torch.full((B, H, S, pitch), fill, dtype=dtype, device="cuda")
+        view = store[..., :d]
+        if x is not None:
+            view.copy_(x)
+        return store, view
+
+    ins = []
+    for x in (Q, K, V, dO):
+        if layout == sa.STRIPED:
+            y = torch.empty_like(x)
+            sa.sa_stripe_permute(x, y, N)
+            x = y
+        ins.append(padded(x, torch.bfloat16, float("nan"))[1])
+    Qv, Kv, Vv, Gv = ins
+    O_store, O = padded(None, torch.float32, float("nan"))
+    LSE = torch.empty(B, H, S, dtype=torch.float32, device="cuda")
+    delta = torch.empty_like(LSE)
+    g_stores, grads = zip(*(padded(None, torch.float32, float("nan")) for _ in range(3)))
+    shape = sa.shard_shape(Qv, c, LSE)
+    assert shape.stride_s == pitch
+    sa.sa_ring_fwd(Qv, Kv, Vv, O, LSE, N, layout, shape)
+    sa.sa_ring_bwd(Qv, Kv, Vv, Gv, O, LSE, delta, *grads, N, layout, shape)
+    torch.cuda.synchronize()
+    for st in (O_store,) + tuple(g_stores):
+        assert bool(torch.isnan(st[..., d:]).all())          # the gap is left alone
+    scale = 1.0 / np.sqrt(d)
+    Oref, Lref = hp.oracle_forward(Q, K, V, scale)
+    back = lambda t: hp.from_device_order_host(t.contiguous().cpu().float().numpy(), N, layout)
+    assert hp.max_abs_err(back(O), Oref) <= 2e-2
+    assert hp.max_abs_err(hp.from_device_order_host(LSE.cpu().numpy(), N, layout), Lref) <= 1e-3
+    for g, w in zip(grads, hp.oracle_backward(Q, K, V, dO, scale)):
+        hp.check_grad("gradient", back(g), w, True)

@@ -4,7 +4,7 @@
 //  (2) the same stream with the VALU, transcendental, LDS-read and global -> LDS tile-load
 //      instructions of an attention inner loop riding along, on registers the MFMAs do not
 //      touch: what the instruction mix allows before any dependency, barrier or memory wait.
-// Build: python -m paper_2311_09431_amd.build --ubench     Run: _build/mfma_ceiling
+// Build: python ubench/build.py     Run: _build/mfma_ceiling
 #include <hip/hip_runtime.h>
 #include <cstdio>
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
