@@ -232,7 +232,7 @@ def cpu_baseline():
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = 1
-    d, S_f, S_b = 128, 32768, 6144
+    d, S_f, S_b = 128, 32768, 8192
     scale = 1.0 / np.sqrt(d)
     q, k, v, g = (inputs.to_f64(x)[0, 0] for x in inputs.qkv(1, 1, S_f, d, 99, torch.bfloat16, with_dout=True))
     t0 = time.perf_counter()
@@ -255,13 +255,10 @@ def cpu_baseline():
 def device_info():
     """Compute units and clock as the runtime reports them, and the bf16 MFMA peak they imply
     (4096 flop per clock and compute unit); the roofline keeps the published 2.5 PFLOP/s."""
-    p = torch.cuda.get_device_properties(0)
-    cus = int(p.multi_processor_count)
-    khz = getattr(p, "clock_rate", None)
-    info = {"name": p.name, "compute_units": cus, "max_clock_mhz": None if not khz else round(khz / 1e3, 1),
-            "hbm_GB": round(p.total_memory / 1e9, 1)}
-    if khz:
-        info["bf16_peak_from_cus_and_clock_tflops"] = round(cus * khz * 1e3 * 4096 / 1e12, 1)
+    cus, khz, mem = sa.sa_device_props()
+    info = {"name": torch.cuda.get_device_name(0), "compute_units": cus, "max_clock_mhz": round(khz / 1e3, 1),
+            "hbm_GB": round(mem / 1e9, 1),
+            "bf16_peak_from_cus_and_clock_tflops": round(cus * khz * 1e3 * 4096 / 1e12, 1)}
     return info
 
 

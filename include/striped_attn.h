@@ -241,6 +241,13 @@ int64_t sa_step_pairs(int32_t q_dev, int32_t kv_dev, int32_t N, int32_t layout, 
 int sa_step_tiles(int32_t q_dev, int32_t kv_dev, int32_t N, int32_t layout, int64_t c,
                   int64_t skip_bq, int64_t skip_bk, int64_t* computed, int64_t* total);
 
+/*
+ * Host-only: compute units, peak engine clock (kHz) and device memory (bytes) of the current
+ * HIP device, as hipGetDeviceProperties reports them; the benchmark prints them beside the
+ * peak it prices against.  Errors: NULL, HIP.
+ */
+int sa_device_props(int32_t* compute_units, int32_t* clock_khz, int64_t* memory_bytes);
+
 /* Human-readable name of a status code; never NULL. */
 const char* sa_status_str(int status);
 

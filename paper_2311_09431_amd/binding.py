@@ -63,6 +63,7 @@ def lib():
                                     ctypes.POINTER(i64)]),
             "sa_step_mask": (i32, [i32, i32, i32, i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]),
             "sa_step_pairs": (i64, [i32, i32, i32, i32, i64]),
+            "sa_device_props": (i32, [ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i64)]),
             "sa_status_str": (ctypes.c_char_p, [i32]),
         }
         for name, (res, args) in sig.items():
@@ -75,7 +76,7 @@ def lib():
 EXPORTS = ("sa_stripe_permute", "sa_unstripe_permute", "sa_rope", "sa_state_init", "sa_attn_step_fwd",
            "sa_finalize", "sa_bwd_preprocess", "sa_attn_step_bwd", "sa_ring_fwd", "sa_ring_bwd",
            "sa_attn_step_fwd_tiled", "sa_attn_step_bwd_tiled", "sa_ring_fwd_tiled", "sa_ring_bwd_tiled",
-           "sa_step_tiles", "sa_step_mask", "sa_step_pairs", "sa_status_str")
+           "sa_step_tiles", "sa_step_mask", "sa_step_pairs", "sa_device_props", "sa_status_str")
 
 
 def _ptr(t):
@@ -242,6 +243,13 @@ def sa_step_mask(q_dev, kv_dev, N, layout):
 
 def sa_step_pairs(q_dev, kv_dev, N, layout, c):
     return lib().sa_step_pairs(q_dev, kv_dev, N, layout, c)
+
+
+def sa_device_props():
+    """(compute units, peak clock in kHz, device memory in bytes) of the current device."""
+    cus, khz, mem = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int64()
+    _check(lib().sa_device_props(ctypes.byref(cus), ctypes.byref(khz), ctypes.byref(mem)), "sa_device_props")
+    return cus.value, khz.value, mem.value
 
 
 def sa_status_str(status):

@@ -393,6 +393,17 @@ int sa_step_tiles(int32_t q_dev, int32_t kv_dev, int32_t N, int32_t layout, int6
     return SA_OK;
 }
 
+int sa_device_props(int32_t* compute_units, int32_t* clock_khz, int64_t* memory_bytes) {
+    if (!compute_units || !clock_khz || !memory_bytes) return SA_ERR_NULL;
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return SA_ERR_HIP;
+    *compute_units = prop.multiProcessorCount;
+    *clock_khz = prop.clockRate;
+    *memory_bytes = (int64_t)prop.totalGlobalMem;
+    return SA_OK;
+}
+
 const char* sa_status_str(int status) {
     switch (status) {
         case SA_OK: return "ok";

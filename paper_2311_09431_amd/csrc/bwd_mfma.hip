@@ -273,11 +273,20 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
 __device__ inline void mfma_results_to_valu(f32x16& a, f32x16& b) {
     asm volatile("s_nop 15\n\ts_nop 15" : "+v"(a), "+v"(b));
 }
+// The other software-managed hazard is on the input side: a VALU write of a VGPR followed by
+// an MFMA read of it needs 2 wait states (same table).  The operands normally come straight
+// from LDS reads (ordered by s_waitcnt, no hazard); only the PART instantiations pass them
+// through VALU selects first (zero_beyond_d), and then AFTER_VALU puts the wait in front of
+// the instruction.
+template <bool AFTER_VALU>
 __device__ inline void mfma_vgpr_first(f32x16& acc, bf16x8 a, bf16x8 b) {
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "v"(b));
+    if (AFTER_VALU) asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "v"(b));
+    else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "v"(b));
 }
+template <bool AFTER_VALU>
 __device__ inline void mfma_vgpr_acc(f32x16& acc, bf16x8 a, bf16x8 b) {
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+    if (AFTER_VALU) asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+    else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
 }
 
 // A workgroup owns 128 key rows (K and V rows in registers as B operands, dK^T and
@@ -347,9 +356,9 @@ __device__ inline void dkdv_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, 
         if (NEXT && i < KS) {
             const bf16x8 qx = PART ? zero_beyond_d(qa[i], i == part_ks) : qa[i];
             const bf16x8 gx = PART ? zero_beyond_d(ga[i], i == part_ks) : ga[i];
-            if (i == 0) mfma_vgpr_first(s_next, qx, kf[0]);
-            else mfma_vgpr_acc(s_next, qx, kf[i]);
-            mfma_vgpr_acc(dp_next, gx, vf[i]);
+            if (i == 0) mfma_vgpr_first<PART>(s_next, qx, kf[0]);
+            else mfma_vgpr_acc<PART>(s_next, qx, kf[i]);
+            mfma_vgpr_acc<PART>(dp_next, gx, vf[i]);
         }
 #pragma unroll
         for (int r = 2 * i; r < 2 * i + 2; ++r) {
@@ -486,9 +495,9 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
                 qx = zero_beyond_d(qx, ks == part_ks);
                 gx = zero_beyond_d(gx, ks == part_ks);
             }
-            if (ks == 0) mfma_vgpr_first(s_a, qx, kf[0]);
-            else mfma_vgpr_acc(s_a, qx, kf[ks]);
-            mfma_vgpr_acc(dp_a, gx, vf[ks]);
+            if (ks == 0) mfma_vgpr_first<PART>(s_a, qx, kf[0]);
+            else mfma_vgpr_acc<PART>(s_a, qx, kf[ks]);
+            mfma_vgpr_acc<PART>(dp_a, gx, vf[ks]);
         }
         mfma_results_to_valu(s_a, dp_a);
     }

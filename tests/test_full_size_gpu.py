@@ -107,11 +107,13 @@ def _sparse_dout(B, H, S, d, rows, seed):
 # bf16 bound scaled by the gradient's magnitude.  (ii) ||got - want||_F <= 1e-2 ||want||_F per
 # tensor: P and dS are rounded to bf16 (2^-9 relative, about 1e-3 rms) before the fp32-accumulated
 # products, so a correct result sits near 2e-3 whatever the gradient's magnitude, and a dropped
-# tile or term does not.  (iii) the same per 128-row tile with 2e-2, plus a floor of 2e-6 rms per
-# element for rows whose gradient vanishes by cancellation (row 0: dP - delta = 0 exactly);
-# rows whose expected gradient is exactly zero (dO = 0 there, or keys no sampled query sees)
-# must be exactly zero.
-REL_TENSOR, REL_TILE, ABS_TILE_RMS = 1e-2, 2e-2, 2e-6
+# tile or term does not.  (iii) the same per 128-row tile with 2e-2, plus an absolute floor per
+# element of a row that carries a gradient: 2e-6 rms for dK and dV (fp32 accumulation), 1e-3 rms
+# for dQ, where dS = P (dP - delta) cancels on rows with few keys or one dominant key (row 0:
+# exactly zero) and delta carries the forward's bf16 rounding of P (2^-9 of |dP|, against a
+# difference that may be a few per cent of it).  Rows whose expected gradient is exactly zero
+# (dO = 0 there, or keys no sampled query sees) must be exactly zero.
+REL_TENSOR, REL_TILE, ABS_TILE_RMS, ABS_TILE_RMS_DQ = 1e-2, 2e-2, 2e-6, 1e-3
 
 
 def _check_grads(name, got, want, tile=128, report=None, zero_rows=None):
@@ -127,11 +129,13 @@ def _check_grads(name, got, want, tile=128, report=None, zero_rows=None):
     n, d = got.shape[0] // tile * tile, got.shape[1]
     g, w = got[:n].reshape(-1, tile * d), want[:n].reshape(-1, tile * d)
     num, den = np.linalg.norm(g - w, axis=1), np.linalg.norm(w, axis=1)
-    bound = REL_TILE * den + ABS_TILE_RMS * np.sqrt(tile * d)
+    signal_rows = np.any(want[:n] != 0.0, axis=1).reshape(-1, tile).sum(axis=1)
+    floor = (ABS_TILE_RMS_DQ if name.startswith("dQ") else ABS_TILE_RMS) * np.sqrt(signal_rows * d)
+    bound = REL_TILE * den + floor
     worst = int(np.argmax(num - bound))
-    assert num[worst] <= bound[worst], (name, "tile", worst, num[worst], den[worst])
+    assert num[worst] <= bound[worst], (name, "tile", worst, num[worst], den[worst], bound[worst])
     if report is not None:
-        report.append((name, "%.2e" % err, "%.2e" % rel, "%.2e" % float(np.max((num - ABS_TILE_RMS * np.sqrt(tile * d)) / np.maximum(den, 1e-300)))))
+        report.append((name, "%.2e" % err, "%.2e" % rel, "%.2e" % float(np.max(num / np.maximum(den, 1e-300)))))
 
 
 def _chunked_grad(Qh, Kh, Vh, Gh, scale, rows, chunk=512):
