@@ -141,6 +141,24 @@ int sa_attn_step_fwd(const void* q, const void* k, const void* v, float* o, floa
                      const sa_shape* shape, void* stream);
 
 /*
+ * sa_attn_step_fwd with the rotary embedding of the QUERY rows fused into their load (Sec. 2.3:
+ * every token keeps the position id of its original place, so device q_dev's row a carries
+ * id a * N + q_dev under the striped layout; the ids come from running sa_stripe_permute on
+ * 0..n_seq-1).  q holds UNROTATED rows; they are rotated as sa_rope would (same pairing, angle
+ * q_pos[b, a] * rope_base^(-2 i / d), reduced in double precision, result rounded once to
+ * bf16) on their way into the matrix-core operands and nothing is written back.  k must hold
+ * rows already rotated by sa_rope: a key shard is read by every query tile, so rotating it once
+ * per shard is the cheaper place.  q_pos: device int32 [B, c], pos_stride_b elements between
+ * batches (0: one id row shared by all batches).  Forward only: the backward kernels stream Q
+ * through LDS in both products and take rotated tensors from sa_rope.
+ * Shapes: bf16, d = 64 or 128, c a multiple of 128 (the matrix-core forward kernel); anything
+ * else returns SA_ERR_SHAPE.  Other arguments and errors as sa_attn_step_fwd and sa_rope.
+ */
+int sa_attn_step_fwd_rope(const void* q, const void* k, const void* v, float* o, float* lse,
+                          const int32_t* q_pos, int64_t pos_stride_b, float rope_base, int32_t q_dev,
+                          int32_t kv_dev, int32_t N, int32_t layout, const sa_shape* shape, void* stream);
+
+/*
  * End of the ring (Algorithm 1, "normalize"): the running o is kept normalised,
  * so this only rounds fp32 o to `shape->dtype` into `out` (same strides).
  */

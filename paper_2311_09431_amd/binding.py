@@ -50,6 +50,7 @@ def lib():
             "sa_state_init": (i32, [vp, vp, shp, vp]),
             "sa_rope": (i32, [vp, vp, vp, i64, shp, ctypes.c_float, i32, vp]),
             "sa_attn_step_fwd": (i32, [vp, vp, vp, vp, vp, i32, i32, i32, i32, shp, vp]),
+            "sa_attn_step_fwd_rope": (i32, [vp, vp, vp, vp, vp, vp, i64, ctypes.c_float, i32, i32, i32, i32, shp, vp]),
             "sa_finalize": (i32, [vp, vp, shp, vp]),
             "sa_bwd_preprocess": (i32, [vp, vp, vp, shp, vp]),
             "sa_attn_step_bwd": (i32, [vp] * 9 + [i32, i32, i32, i32, shp, vp]),
@@ -74,6 +75,7 @@ def lib():
 
 
 EXPORTS = ("sa_stripe_permute", "sa_unstripe_permute", "sa_rope", "sa_state_init", "sa_attn_step_fwd",
+           "sa_attn_step_fwd_rope",
            "sa_finalize", "sa_bwd_preprocess", "sa_attn_step_bwd", "sa_ring_fwd", "sa_ring_bwd",
            "sa_attn_step_fwd_tiled", "sa_attn_step_bwd_tiled", "sa_ring_fwd_tiled", "sa_ring_bwd_tiled",
            "sa_step_tiles", "sa_step_mask", "sa_step_pairs", "sa_device_props", "sa_status_str")
@@ -161,6 +163,17 @@ def sa_state_init(o, lse, shape):
 def sa_attn_step_fwd(q, k, v, o, lse, q_dev, kv_dev, N, layout, shape):
     _check(lib().sa_attn_step_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), q_dev, kv_dev, N,
                                   layout, ctypes.byref(shape), _stream()), "sa_attn_step_fwd")
+
+
+def sa_attn_step_fwd_rope(q, k, v, o, lse, q_pos, q_dev, kv_dev, N, layout, shape, base=10000.0):
+    """Forward step with the query rows rotated by q_pos (int32 [c] or [B, c]) as they are loaded;
+    k must already be rotated (sa_rope)."""
+    if q_pos.dtype != torch.int32 or not q_pos.is_contiguous():
+        raise TypeError("q_pos must be a contiguous int32 tensor")
+    stride_b = q_pos.stride(0) if q_pos.dim() == 2 else 0
+    _check(lib().sa_attn_step_fwd_rope(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(q_pos), stride_b,
+                                       float(base), q_dev, kv_dev, N, layout, ctypes.byref(shape), _stream()),
+           "sa_attn_step_fwd_rope")
 
 
 def sa_finalize(o, out, shape):

@@ -116,12 +116,17 @@ int check_skip(const sa_shape* s, int bq, int bk) {
 }
 
 int step_fwd(const void* q, const void* k, const void* v, float* o, float* lse, int q_dev, int kv_dev,
-             int layout, const sa_shape* s, int bq, int bk, hipStream_t st) {
+             int layout, const sa_shape* s, int bq, int bk, hipStream_t st, const int32_t* q_pos = nullptr,
+             int64_t pos_stride_b = 0, float rope_base = 0.f) {
     StepArgs a = make_args(s);
     classify(q_dev, kv_dev, layout, &a.kind, &a.off);
-    if (a.kind == sa::MASK_EMPTY) return SA_OK;   // entirely masked block: nothing to launch
     a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse;
     a.skip_bq = bq; a.skip_bk = bk;
+    if (q_pos) {
+        if (!sa::fwd_mfma_rope_supported(a, s->dtype)) return SA_ERR_SHAPE;
+        a.q_pos = q_pos; a.pos_stride_b = pos_stride_b; a.rope_log2_base = log2((double)rope_base);
+    }
+    if (a.kind == sa::MASK_EMPTY) return SA_OK;   // entirely masked block: nothing to launch
     hipError_t e = sa::fwd_mfma_supported(a, s->dtype) ? sa::launch_fwd_mfma(a, st)
                                                        : sa::launch_fwd_generic(a, s->dtype, st);
     return e == hipSuccess ? SA_OK : SA_ERR_HIP;
@@ -211,6 +216,20 @@ int sa_attn_step_fwd_tiled(const void* q, const void* k, const void* v, float* o
     if (int e = check_skip(shape, skip_bq, skip_bk)) return e;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return SA_ERR_ALIGN;
     return step_fwd(q, k, v, o, lse, q_dev, kv_dev, layout, shape, skip_bq, skip_bk, (hipStream_t)stream);
+}
+
+int sa_attn_step_fwd_rope(const void* q, const void* k, const void* v, float* o, float* lse,
+                          const int32_t* q_pos, int64_t pos_stride_b, float rope_base, int32_t q_dev,
+                          int32_t kv_dev, int32_t N, int32_t layout, const sa_shape* shape, void* stream) {
+    if (!q || !k || !v || !o || !lse || !q_pos) return SA_ERR_NULL;
+    if (int e = check_shape(shape)) return e;
+    if (int e = check_step(q_dev, kv_dev, N, layout)) return e;
+    if (pos_stride_b < 0 || (pos_stride_b > 0 && pos_stride_b < shape->c) || !(rope_base > 1.f)) return SA_ERR_SHAPE;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) ||
+        (reinterpret_cast<uintptr_t>(q_pos) & 3u))
+        return SA_ERR_ALIGN;
+    return step_fwd(q, k, v, o, lse, q_dev, kv_dev, layout, shape, 0, 0, (hipStream_t)stream, q_pos,
+                    pos_stride_b, rope_base);
 }
 
 int sa_attn_step_fwd(const void* q, const void* k, const void* v, float* o, float* lse, int32_t q_dev,

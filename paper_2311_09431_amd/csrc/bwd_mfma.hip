@@ -339,7 +339,9 @@ __device__ inline void dkdv_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, 
     auto fetch_stat = [&](int i) {
         lv[i] = *reinterpret_cast<const float2*>(stat_cur + 8 * (i / 2) + 4 * h + 2 * (i % 2));
     };
-    constexpr int AHEAD = 2;
+    // operands requested this many slices ahead of their use: row reads 2, transposed reads 3
+    // (3 / 4 and 4 / 5 measured the same to 1 % at 32768-token shards: LDS latency is covered)
+    constexpr int AHEAD = 2, TAHEAD = 3;
 #pragma unroll
     for (int i = 0; i < AHEAD; ++i) {
         fetch(i);
@@ -352,7 +354,7 @@ __device__ inline void dkdv_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, 
             fetch(i + AHEAD);
             fetch_stat(i + AHEAD);
         }
-        if (i >= 5) fetch_t(i - 5);                 // transposed operands 0..2 ahead of their use
+        if (i >= 8 - TAHEAD) fetch_t(i - (8 - TAHEAD));     // the first transposed operands ahead of their use
         if (NEXT && i < KS) {
             const bf16x8 qx = PART ? zero_beyond_d(qa[i], i == part_ks) : qa[i];
             const bf16x8 gx = PART ? zero_beyond_d(ga[i], i == part_ks) : ga[i];
@@ -372,7 +374,7 @@ __device__ inline void dkdv_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, 
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        if (i + 3 < 8) fetch_t(i + 3);
+        if (i + TAHEAD < 8) fetch_t(i + TAHEAD);
         if (i % 4 < MB) {
             accv[i % 4] = mfma(gt[i], pb[i / 4], accv[i % 4]);
             acck[i % 4] = mfma(qt[i], dsb[i / 4], acck[i % 4]);

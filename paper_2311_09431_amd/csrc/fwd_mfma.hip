@@ -192,6 +192,29 @@ __device__ inline void step(f32x16& s_cur, f32x16& s_next, bf16x8 (&p_cur)[2], b
     }
 }
 
+// Rotary embedding of a query row held as B-operand fragments (Sec. 2.3: a token keeps the
+// position id of its original place, whatever device it sits on).  Rotate-half pairing: column
+// i < d/2 with column i + d/2; with d == DP both sit in the same lane, KS/2 fragments apart.
+// turns[i] = base^(-2i/d) / (2 pi) in double precision (LDS, filled once per workgroup); the
+// angle in revolutions is reduced to [-1/2, 1/2] in double (position ids reach 10^6, where an
+// fp32 angle is off by 0.05 rad) and only then handed to the fp32 sine / cosine instructions,
+// which take revolutions.
+template <int DP>
+__device__ inline void rope_rotate(bf16x8 (&f)[8], const double* turns, int pos, int h) {
+    constexpr int KS = DP / 16;
+#pragma unroll
+    for (int ks = 0; ks < KS / 2; ++ks)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const double t = (double)pos * turns[16 * ks + 8 * h + e];
+            const float r = (float)(t - rint(t));
+            const float sn = __builtin_amdgcn_sinf(r), cs = __builtin_amdgcn_cosf(r);
+            const float lo = (float)f[ks][e], hi = (float)f[ks + KS / 2][e];
+            f[ks][e] = (__bf16)fmaf(lo, cs, -hi * sn);
+            f[ks + KS / 2][e] = (__bf16)fmaf(hi, cs, lo * sn);
+        }
+}
+
 // One code path serves every step: a block is walked up to the last key tile that holds an
 // allowed pair, and the last BM / 64 tiles of the walk carry the element mask.  For a
 // triangular block the mask limit is the query's own position; for a full block (contiguous
@@ -202,10 +225,12 @@ __device__ inline void step(f32x16& s_cur, f32x16& s_next, bf16x8 (&p_cur)[2], b
 // them).
 // (FULL is a template argument rather than a launch argument so that profiler traces name
 // triangular and full launches apart; the code is the same.)
-template <bool RAGGED, bool FULL, int DP, bool PART>
+// ROPE: the query rows are rotated by their position ids as they are loaded (d == DP).
+template <bool RAGGED, bool FULL, int DP, bool PART, bool ROPE = false>
 __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1)
 fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     constexpr int KS = DP / 16, MB = DP / 32;
+    __shared__ double rope_turns[ROPE ? DP / 2 : 1];
     // one LDS object per tile buffer
     __shared__ __attribute__((aligned(1024))) char k_lds0[TILE_BYTES];
     __shared__ __attribute__((aligned(1024))) char k_lds1[TILE_BYTES];
@@ -281,6 +306,11 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
 
     bf16x8 qf[8];
     load_b_frags(qf, Q + (int64_t)a * ss, h, d);
+    int q_position = 0;
+    if (ROPE) {
+        q_position = p.q_pos[b * p.pos_stride_b + a];
+        if (tid < DP / 2) rope_turns[tid] = exp2(-2.0 * tid / DP * p.rope_log2_base) * 0.15915494309189535;
+    }
     const float kappa = p.scale * LOG2E;
     float m = L[a] * LOG2E;                   // -inf stays -inf
     float l = (h == 0) ? 1.f : 0.f;           // the two half-waves hold partial row sums
@@ -298,6 +328,7 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
 
     __builtin_amdgcn_s_waitcnt(0);     // the direct loads have landed (vmcnt) ...
     __syncthreads();                   // ... for every wavefront
+    if (ROPE) rope_rotate<DP>(qf, rope_turns, q_position, h);
 
     // PART: k-step whose fragment, in this half-wave, is the chunk holding column d
     const int part_ks = (PART && ((d >> 3) & 1) == h) ? (d >> 4) : -1;
@@ -429,13 +460,27 @@ void launch_fwd_variant(const StepArgs& a, hipStream_t st, dim3 grid, dim3 block
         else hipLaunchKernelGGL((fwd_mfma_kernel<false, false, DP, PART>), grid, block, 0, st, a, n_qtiles);
     }
 }
+template <int DP>
+void launch_fwd_rope(const StepArgs& a, hipStream_t st, dim3 grid, dim3 block, int n_qtiles) {
+    if (a.kind == MASK_FULL) hipLaunchKernelGGL((fwd_mfma_kernel<false, true, DP, false, true>), grid, block, 0, st, a, n_qtiles);
+    else hipLaunchKernelGGL((fwd_mfma_kernel<false, false, DP, false, true>), grid, block, 0, st, a, n_qtiles);
+}
 }  // namespace
+
+// fused query rotation: head dimension 64 or 128 (both halves of a rotation pair in one lane)
+// and block sizes that are a multiple of 128
+bool fwd_mfma_rope_supported(const StepArgs& a, int dtype) {
+    return fwd_mfma_supported(a, dtype) && (a.d == 64 || a.d == 128) && a.c % BM == 0;
+}
 
 hipError_t launch_fwd_mfma(const StepArgs& a, hipStream_t st) {
     const int n_qtiles = (a.c + BM - 1) / BM;
     const dim3 grid((unsigned)n_qtiles * a.B * a.H), block(64 * NW);
     const bool part = a.d % 8 != 0;
-    if (a.d <= 64) {
+    if (a.q_pos) {
+        if (a.d == 64) launch_fwd_rope<64>(a, st, grid, block, n_qtiles);
+        else launch_fwd_rope<128>(a, st, grid, block, n_qtiles);
+    } else if (a.d <= 64) {
         if (part) launch_fwd_variant<64, true>(a, st, grid, block, n_qtiles);
         else launch_fwd_variant<64, false>(a, st, grid, block, n_qtiles);
     } else {

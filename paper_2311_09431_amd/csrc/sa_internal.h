@@ -41,6 +41,13 @@ struct StepArgs {
     // at least one allowed pair is computed (masked elements contribute exact zeros).
     // Both are multiples of 128 that divide c.
     int skip_bq, skip_bk;
+    // Forward only, MFMA kernels only: rotary embedding of the QUERY rows applied while they
+    // are loaded (q holds unrotated rows; k is expected rotated already).  q_pos: position ids
+    // of the c query rows per batch (int32, pos_stride_b elements between batches, 0 = shared),
+    // NULL = no rotation.  rope_log2_base = log2 of the frequency base.
+    const int32_t* q_pos;
+    int64_t pos_stride_b;
+    double rope_log2_base;
 };
 
 // launchers: return hipSuccess or the launch error
@@ -57,6 +64,7 @@ hipError_t launch_rope(const void* x, void* y, const int32_t* pos, int64_t pos_s
 hipError_t launch_fwd_generic(const StepArgs& a, int dtype, hipStream_t st);
 hipError_t launch_bwd_generic(const StepArgs& a, int dtype, hipStream_t st);
 bool fwd_mfma_supported(const StepArgs& a, int dtype);
+bool fwd_mfma_rope_supported(const StepArgs& a, int dtype);
 hipError_t launch_fwd_mfma(const StepArgs& a, hipStream_t st);
 bool bwd_mfma_supported(const StepArgs& a, int dtype);
 hipError_t launch_bwd_mfma(const StepArgs& a, hipStream_t st);

@@ -96,3 +96,63 @@ def test_striped_ring_attention_on_rotated_inputs():
     # and the rotated bits are what the oracle's rope gives for the original order
     want_q = orc.rope(inputs.to_f64(Q), np.arange(S))
     assert hp.max_abs_err(Qr, want_q) <= 2 ** -8 * max(1.0, float(np.abs(want_q).max()))
+
+
+@pytest.mark.parametrize("layout", [sa.CONTIGUOUS, sa.STRIPED])
+@pytest.mark.parametrize("d", [128, 64])
+def test_query_rotation_fused_into_the_forward_step(layout, d):
+    # sa_attn_step_fwd_rope rotates the query rows as it loads them; keys are rotated once per
+    # shard by sa_rope.  Against the oracle: rotate in fp64, round the rotated queries to bf16
+    # (the precision in which the kernel hands them to the matrix cores), attention on that.
+    B, H, S, N = 2, 2, 1024, 4
+    c = S // N
+    Q, K, V = inputs.qkv(B, H, S, d, 70 + d, torch.bfloat16)
+    ids = np.arange(S, dtype=np.int32) * 700 + 3            # positions up to 7 * 10^5
+    pos = torch.from_numpy(ids).cuda()
+    Qp, Kp, Vp = (hp.to_device_order(x.cuda(), N, layout) for x in (Q, K, V))
+    pos_p = pos
+    if layout == sa.STRIPED:
+        pos_p = torch.empty_like(pos)
+        sa.sa_stripe_permute(pos, pos_p, N, seq_axis=0)      # the ids travel with the tokens
+    full = sa.shard_shape(Kp, S)
+    Kr = torch.empty_like(Kp)
+    sa.sa_rope(Kp, Kr, pos_p, full)
+    Qr = torch.empty_like(Qp)
+    sa.sa_rope(Qp, Qr, pos_p, full)
+    outs = []
+    for fused in (True, False):
+        O = torch.empty(B, H, S, d, dtype=torch.float32, device="cuda")
+        LSE = torch.empty(B, H, S, dtype=torch.float32, device="cuda")
+        shape = sa.shard_shape(Qp, c, LSE)
+        r = lambda t, dev: t[:, :, dev * c:]
+        for j in range(N):
+            sa.sa_state_init(r(O, j), r(LSE, j), shape)
+            for k in range(N):
+                if fused:
+                    sa.sa_attn_step_fwd_rope(r(Qp, j), r(Kr, k), r(Vp, k), r(O, j), r(LSE, j),
+                                             pos_p[j * c:(j + 1) * c], j, k, N, layout, shape)
+                else:
+                    sa.sa_attn_step_fwd(r(Qr, j), r(Kr, k), r(Vp, k), r(O, j), r(LSE, j), j, k, N, layout, shape)
+        outs.append((O, LSE))
+    torch.cuda.synchronize()
+    scale = 1.0 / np.sqrt(d)
+    q_rot = torch.from_numpy(orc.rope(inputs.to_f64(Q), ids)).to(torch.bfloat16)
+    k_rot = hp.from_device_order_host(inputs.to_f64(Kr), N, layout)       # the bits the kernel read
+    Ow, Lw = orc.causal_attention_bh(inputs.to_f64(q_rot), k_rot, inputs.to_f64(V), scale)
+    for O, LSE in outs:
+        assert hp.max_abs_err(hp.from_device_order_host(O.cpu().numpy(), N, layout), Ow) <= 2e-2
+        assert hp.max_abs_err(hp.from_device_order_host(LSE.cpu().numpy(), N, layout), Lw) <= 1e-3
+    # fused and unfused differ only where the two sine / cosine evaluations round a rotated
+    # query to neighbouring bf16 values
+    assert hp.max_abs_err(outs[0][0].cpu().numpy(), outs[1][0].cpu().numpy()) <= 2e-3
+    assert hp.max_abs_err(outs[0][1].cpu().numpy(), outs[1][1].cpu().numpy()) <= 5e-4
+
+
+def test_fused_query_rotation_rejects_other_shapes():
+    q = torch.zeros(1, 1, 256, 100, dtype=torch.bfloat16, device="cuda")
+    o = torch.zeros(1, 1, 256, 100, device="cuda")
+    lse = torch.zeros(1, 1, 256, device="cuda")
+    pos = torch.zeros(256, dtype=torch.int32, device="cuda")
+    with pytest.raises(sa.StripedAttnError) as e:
+        sa.sa_attn_step_fwd_rope(q, q, q, o, lse, pos, 0, 0, 1, sa.STRIPED, sa.shard_shape(q, 256, lse))
+    assert e.value.status == -2
