@@ -10,7 +10,7 @@ inputs resident in HBM.  The contiguous (Ring Attention) layout is timed beside
 it for the worst-device step latencies the paper's argument is about (Sec. 1:
 a round lasts as long as its slowest device).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3|cfg2|cfg4|cfg5|3b|tiny]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3|cfg2|cfg4|cfg5|3b|d64|d256|tiny]
                     [--bwd 0|1] [--cold] [--graph] [--skip-granularity BQxBK] [--kv-heads H_KV]
 
 Prints one JSON line.
@@ -73,7 +73,13 @@ WORKLOADS = {
                       "q_dev 15"),
     "3b": dict(B=1, H=32, d=100, S=262144, N=8, q_dev=7,
                desc="cfg3 with the head dimension of Table 1's 3B model: B1 H32 d100 S262144 N8, bf16, "
-                    "q_dev 7 (matrix-core kernels, columns zero-padded to 128)"),
+                    "q_dev 7 (matrix-core kernels, 128 columns computed)"),
+    "d64": dict(B=1, H=32, d=64, S=262144, N=8, q_dev=7,
+                desc="cfg3 with head dimension 64: B1 H32 d64 S262144 N8, bf16, q_dev 7 (matrix-core kernels, "
+                     "64 columns computed)"),
+    "d256": dict(B=1, H=16, d=256, S=262144, N=8, q_dev=7,
+                 desc="cfg3's model width with head dimension 256: B1 H16 d256 S262144 N8, bf16, q_dev 7 "
+                      "(matrix-core kernels, two 128-column halves)"),
     "tiny": dict(B=1, H=2, d=128, S=4096, N=4, q_dev=-1, desc="B1 H2 d128 S4096 N4, bf16 (quick check)"),
 }
 

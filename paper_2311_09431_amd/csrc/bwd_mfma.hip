@@ -51,27 +51,37 @@ __device__ inline bf16x8 pack8(const f32x16& x, int first) {
 // Two barriers per 64-key tile: one makes the tile requested one iteration earlier
 // visible, one releases the tile just finished for the next request.
 
-// DP: columns computed (128, or 64 for head dimensions up to 64: k-steps 4..7 of the S and dP
-// products and column blocks 2, 3 of the dQ product do not exist then).  PART: d % 8 == 4, the
-// K and V fragments that hold column d are cleared beyond it (part_ks = the k-step, or -1 for
-// the lanes of the other half-wave).
+// DP: columns computed.  64 for head dimensions up to 64 (k-steps 4..7 of the S and dP
+// products and column blocks 2, 3 of the dQ product do not exist then), 128, or 256 for head
+// dimensions above 128: the K and V tiles then come as two 128-column halves, DT_BYTES apart in
+// LDS, and every slice holds one MFMA of each product per half.  PART: d % 8 == 4, the K and V
+// fragments that hold column d are cleared beyond it (part_ks = the k-step, or -1 for the lanes
+// of the other half-wave).
+constexpr int halves_of(int DP) { return DP > 128 ? 2 : 1; }
 template <bool NEXT, bool MASK, int DP, bool PART>
 __device__ inline void dq_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, f32x16& dp_next,
-                               f32x16 (&acc)[4], const bf16x8 (&qf)[8], const bf16x8 (&gf)[8],
-                               float kappa, float lse2, float delta, const uint32_t (&arow)[8],
-                               const uint32_t (&tr0)[4], const uint32_t (&tr1)[4],
+                               f32x16 (&acc)[4 * halves_of(DP)], const bf16x8 (&qf)[8 * halves_of(DP)],
+                               const bf16x8 (&gf)[8 * halves_of(DP)], float kappa, float lse2, float delta,
+                               const uint32_t (&arow)[8], const uint32_t (&tr0)[4], const uint32_t (&tr1)[4],
                                const char* k_next, const char* v_next, const char* k_cur, int mask_lim,
                                int part_ks) {
-    constexpr int KS = DP / 16, MB = DP / 32;
-    bf16x8 ka[8], va[8], kt[8], dsb[2];
+    constexpr int NH = halves_of(DP), KS = DP / NH / 16, MB = DP / NH / 32;      // per half
+    bf16x8 ka[NH][8], va[NH][8], kt[NH][8], dsb[2];
     auto fetch = [&](int i) {
         if (NEXT && i < KS) {
-            ka[i] = dt_read_row(k_next, arow[i]);
-            va[i] = dt_read_row(v_next, arow[i]);
+#pragma unroll
+            for (int hh = 0; hh < NH; ++hh) {
+                ka[hh][i] = dt_read_row(k_next + hh * DT_BYTES, arow[i]);
+                va[hh][i] = dt_read_row(v_next + hh * DT_BYTES, arow[i]);
+            }
         }
     };
     auto fetch_t = [&](int i) {
-        if (i % 4 < MB) kt[i] = dt_read_tr(k_cur + (i / 4) * 16 * 256, tr0[i % 4], tr1[i % 4]);
+        if (i % 4 < MB) {
+#pragma unroll
+            for (int hh = 0; hh < NH; ++hh)
+                kt[hh][i] = dt_read_tr(k_cur + hh * DT_BYTES + (i / 4) * 16 * 256, tr0[i % 4], tr1[i % 4]);
+        }
     };
     fetch(0);
     fetch(1);
@@ -85,8 +95,12 @@ __device__ inline void dq_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, f3
         if (i + 2 < 8) fetch(i + 2);
         if (i >= 4) fetch_t(i - 4);                 // first half of the K^T operands
         if (NEXT && i < KS) {
-            s_next = mfma(PART ? zero_beyond_d(ka[i], i == part_ks) : ka[i], qf[i], s_next);
-            dp_next = mfma(PART ? zero_beyond_d(va[i], i == part_ks) : va[i], gf[i], dp_next);
+#pragma unroll
+            for (int hh = 0; hh < NH; ++hh) {
+                const bool last_chunk = 8 * hh + i == part_ks;
+                s_next = mfma(PART ? zero_beyond_d(ka[hh][i], last_chunk) : ka[hh][i], qf[8 * hh + i], s_next);
+                dp_next = mfma(PART ? zero_beyond_d(va[hh][i], last_chunk) : va[hh][i], gf[8 * hh + i], dp_next);
+            }
         }
 #pragma unroll
         for (int r = 2 * i; r < 2 * i + 2; ++r) {
@@ -99,7 +113,10 @@ __device__ inline void dq_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, f3
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         if (i + 4 < 8) fetch_t(i + 4);
-        if (i % 4 < MB) acc[i % 4] = mfma(kt[i], dsb[i / 4], acc[i % 4]);
+        if (i % 4 < MB) {
+#pragma unroll
+            for (int hh = 0; hh < NH; ++hh) acc[4 * hh + i % 4] = mfma(kt[hh][i], dsb[i / 4], acc[4 * hh + i % 4]);
+        }
         __builtin_amdgcn_sched_barrier(0);
     }
 }
@@ -112,14 +129,14 @@ __device__ inline void dq_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, f3
 // (FULL is a template argument rather than a launch argument so that profiler traces name
 // triangular and full launches apart; the code is the same.)
 template <bool RAGGED, bool FULL, int DP, bool PART>
-__global__ void __launch_bounds__(256, 2)
+__global__ void __launch_bounds__(256, DP > 128 ? 1 : 2)
 bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
-    constexpr int KS = DP / 16, MB = DP / 32;
-    // one LDS object per tile buffer
-    __shared__ __attribute__((aligned(1024))) char k_lds0[DT_BYTES];
-    __shared__ __attribute__((aligned(1024))) char k_lds1[DT_BYTES];
-    __shared__ __attribute__((aligned(1024))) char v_lds0[DT_BYTES];
-    __shared__ __attribute__((aligned(1024))) char v_lds1[DT_BYTES];
+    constexpr int NH = halves_of(DP), KS = DP / NH / 16, MB = DP / 32;      // k-steps per half, column blocks
+    // one LDS object per tile buffer (two 128-column halves each when DP = 256)
+    __shared__ __attribute__((aligned(1024))) char k_lds0[DT_BYTES * NH];
+    __shared__ __attribute__((aligned(1024))) char k_lds1[DT_BYTES * NH];
+    __shared__ __attribute__((aligned(1024))) char v_lds0[DT_BYTES * NH];
+    __shared__ __attribute__((aligned(1024))) char v_lds1[DT_BYTES * NH];
 
     const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, h = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform, kept scalar
@@ -132,7 +149,7 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
     const int64_t kv_base = b * p.kv_stride_b + (hd / (p.H / p.H_kv)) * p.kv_stride_h;
     const int64_t sbase = b * p.stat_stride_b + hd * p.stat_stride_h;
     const __bf16* Q = (const __bf16*)p.q + base;
-    const int d = p.d;                                 // d <= 128, zero-padded to 128 columns
+    const int d = p.d;                                 // d <= DP, zero-padded to DP columns
     const int64_t ss = p.stride_s;                     // elements between consecutive rows of Q, dO, dQ
     const int pitch = 2 * (int)p.kv_stride_s;          // bytes between consecutive rows of K and V
     const int tile_pitch = DT_ROWS * pitch;            // bytes between 64-row tiles in global memory
@@ -156,24 +173,29 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
     // sub-tile v: allowed iff 8 (r/4) + r%4 <= mask_base - 32 v
     const int mask_base = (full_block ? p.c - 1 : a_own - p.off) - 4 * h;
 
-    uint32_t arow[8], tr0[4], tr1[4], gl[4];
+    uint32_t arow[8], tr0[4], tr1[4], gl[NH][4];
     dt_row_addrs(arow, n, h);
     dt_tr_addrs(tr0, tr1, lane);
-    dt_load_offsets(gl, lane, wave, pitch, d);
-    dt_load(Kr, 0, k_lds0, gl, wave);
-    dt_load(Vr, 0, v_lds0, gl, wave);
-    dt_load(Kr, tile_pitch, k_lds1, gl, wave);       // n_kt >= 2 always
-    dt_load(Vr, tile_pitch, v_lds1, gl, wave);
+#pragma unroll
+    for (int hh = 0; hh < NH; ++hh) dt_load_offsets(gl[hh], lane, wave, pitch, d, hh);
+    auto load_tile = [&](dt_rsrc m, int tile_byte_offset, char* buf) {
+#pragma unroll
+        for (int hh = 0; hh < NH; ++hh) dt_load(m, tile_byte_offset, buf + hh * DT_BYTES, gl[hh], wave);
+    };
+    load_tile(Kr, 0, k_lds0);
+    load_tile(Vr, 0, v_lds0);
+    load_tile(Kr, tile_pitch, k_lds1);       // n_kt >= 2 always
+    load_tile(Vr, tile_pitch, v_lds1);
 
-    bf16x8 qf[8], gf[8];
-    load_b_frags(qf, Q + (int64_t)a * ss, h, d);
-    load_b_frags(gf, G + (int64_t)a * ss, h, d);
+    bf16x8 qf[8 * NH], gf[8 * NH];
+    load_b_frags<8 * NH>(qf, Q + (int64_t)a * ss, h, d);
+    load_b_frags<8 * NH>(gf, G + (int64_t)a * ss, h, d);
     const float kappa = p.scale * LOG2E;
     float lse2 = p.lse[sbase + a] * LOG2E;
     float delta = p.delta[sbase + a];
-    f32x16 acc[4];
+    f32x16 acc[4 * NH];
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
+    for (int mb = 0; mb < 4 * NH; ++mb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[mb][r] = 0.f;
 
@@ -190,11 +212,14 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) s_a[r] = dp_a[r] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const bf16x8 ka = dt_read_row(k_lds0, arow[ks]), va = dt_read_row(v_lds0, arow[ks]);
-            s_a = mfma(PART ? zero_beyond_d(ka, ks == part_ks) : ka, qf[ks], s_a);
-            dp_a = mfma(PART ? zero_beyond_d(va, ks == part_ks) : va, gf[ks], dp_a);
-        }
+        for (int hh = 0; hh < NH; ++hh)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const bf16x8 ka = dt_read_row(k_lds0 + hh * DT_BYTES, arow[ks]);
+                const bf16x8 va = dt_read_row(v_lds0 + hh * DT_BYTES, arow[ks]);
+                s_a = mfma(PART ? zero_beyond_d(ka, 8 * hh + ks == part_ks) : ka, qf[8 * hh + ks], s_a);
+                dp_a = mfma(PART ? zero_beyond_d(va, 8 * hh + ks == part_ks) : va, gf[8 * hh + ks], dp_a);
+            }
     }
 
     // Trip t = iterations 2t (scores in *_a) and 2t+1 (scores in *_b); PAR = t & 1 selects
@@ -218,8 +243,8 @@ bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
         if (!LAST) {
             __syncthreads();                    // every wavefront is done with tile t
             if (t + 2 < n_kt) {
-                dt_load(Kr, (t + 2) * tile_pitch, k_cur, gl, wave);
-                dt_load(Vr, (t + 2) * tile_pitch, v_cur, gl, wave);
+                load_tile(Kr, (t + 2) * tile_pitch, k_cur);
+                load_tile(Vr, (t + 2) * tile_pitch, v_cur);
             }
         }
     };
@@ -277,7 +302,8 @@ __device__ inline void mfma_results_to_valu(f32x16& a, f32x16& b) {
 // an MFMA read of it needs 2 wait states (same table).  The operands normally come straight
 // from LDS reads (ordered by s_waitcnt, no hazard); only the PART instantiations pass them
 // through VALU selects first (zero_beyond_d), and then AFTER_VALU puts the wait in front of
-// the instruction.
+// the instruction.  The DP = 256 instantiation does the same: it is over the register budget,
+// and the copies the compiler inserts to bring an operand back into a VGPR are VALU writes.
 template <bool AFTER_VALU>
 __device__ inline void mfma_vgpr_first(f32x16& acc, bf16x8 a, bf16x8 b) {
     if (AFTER_VALU) asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "v"(b));
@@ -311,21 +337,29 @@ __device__ inline void load_neg_delta(f32x16& dp, const float* neg_delta, int h)
     }
 }
 
+// DP = 256 (head dimensions above 128): the Q and dO tiles come as two 128-column halves,
+// DT_BYTES apart in LDS.  S and dP contract over both; a workgroup accumulates only ONE half of
+// the columns of dK^T and dV^T (256 columns of both do not fit the register file beside K, V and
+// the score tiles), so tr0 / tr1 arrive with that half's LDS offset added and the other half is
+// another workgroup's, which computes S and dP again.
 template <bool NEXT, bool MASK, int DP, bool PART>
 __device__ inline void dkdv_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, f32x16& dp_next,
-                                 f32x16 (&acck)[4], f32x16 (&accv)[4], const bf16x8 (&kf)[8],
-                                 const bf16x8 (&vf)[8], float kappa, const uint32_t (&arow)[8],
+                                 f32x16 (&acck)[4], f32x16 (&accv)[4], const bf16x8 (&kf)[8 * halves_of(DP)],
+                                 const bf16x8 (&vf)[8 * halves_of(DP)], float kappa, const uint32_t (&arow)[8],
                                  const uint32_t (&tr0)[4], const uint32_t (&tr1)[4], const char* q_next,
                                  const char* g_next, const char* q_cur, const char* g_cur,
                                  const float* stat_cur, const float* stat_next, int h, int mask_lim,
                                  int part_ks) {
-    constexpr int KS = DP / 16, MB = DP / 32;
-    bf16x8 qa[8], ga[8], qt[8], gt[8], pb[2], dsb[2];
+    constexpr int NH = halves_of(DP), KS = DP / NH / 16, MB = DP / NH / 32;      // per half
+    bf16x8 qa[NH][8], ga[NH][8], qt[8], gt[8], pb[2], dsb[2];
     if (NEXT) load_neg_delta(dp_next, stat_next + DT_ROWS, h);
     auto fetch = [&](int i) {
         if (NEXT && i < KS) {
-            qa[i] = dt_read_row(q_next, arow[i]);
-            ga[i] = dt_read_row(g_next, arow[i]);
+#pragma unroll
+            for (int hh = 0; hh < NH; ++hh) {
+                qa[hh][i] = dt_read_row(q_next + hh * DT_BYTES, arow[i]);
+                ga[hh][i] = dt_read_row(g_next + hh * DT_BYTES, arow[i]);
+            }
         }
     };
     auto fetch_t = [&](int i) {
@@ -356,11 +390,14 @@ __device__ inline void dkdv_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, 
         }
         if (i >= 8 - TAHEAD) fetch_t(i - (8 - TAHEAD));     // the first transposed operands ahead of their use
         if (NEXT && i < KS) {
-            const bf16x8 qx = PART ? zero_beyond_d(qa[i], i == part_ks) : qa[i];
-            const bf16x8 gx = PART ? zero_beyond_d(ga[i], i == part_ks) : ga[i];
-            if (i == 0) mfma_vgpr_first<PART>(s_next, qx, kf[0]);
-            else mfma_vgpr_acc<PART>(s_next, qx, kf[i]);
-            mfma_vgpr_acc<PART>(dp_next, gx, vf[i]);
+#pragma unroll
+            for (int hh = 0; hh < NH; ++hh) {
+                const bf16x8 qx = PART ? zero_beyond_d(qa[hh][i], 8 * hh + i == part_ks) : qa[hh][i];
+                const bf16x8 gx = PART ? zero_beyond_d(ga[hh][i], 8 * hh + i == part_ks) : ga[hh][i];
+                if (i == 0 && hh == 0) mfma_vgpr_first<PART || (DP > 128)>(s_next, qx, kf[0]);
+                else mfma_vgpr_acc<PART || (DP > 128)>(s_next, qx, kf[8 * hh + i]);
+                mfma_vgpr_acc<PART || (DP > 128)>(dp_next, gx, vf[8 * hh + i]);
+            }
         }
 #pragma unroll
         for (int r = 2 * i; r < 2 * i + 2; ++r) {
@@ -389,26 +426,27 @@ __device__ inline void dkdv_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, 
 template <bool TRI, bool RAGGED, int DP, bool PART>
 __global__ void __launch_bounds__(256, 1)
 bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
-    constexpr int KS = DP / 16, MB = DP / 32;
-    // one LDS object per tile buffer
-    __shared__ __attribute__((aligned(1024))) char q_lds0[DT_BYTES];
-    __shared__ __attribute__((aligned(1024))) char q_lds1[DT_BYTES];
-    __shared__ __attribute__((aligned(1024))) char g_lds0[DT_BYTES];
-    __shared__ __attribute__((aligned(1024))) char g_lds1[DT_BYTES];
+    constexpr int NH = halves_of(DP), KS = DP / NH / 16, MB = DP / NH / 32;      // per half
+    // one LDS object per tile buffer (two 128-column halves each when DP = 256)
+    __shared__ __attribute__((aligned(1024))) char q_lds0[DT_BYTES * NH];
+    __shared__ __attribute__((aligned(1024))) char q_lds1[DT_BYTES * NH];
+    __shared__ __attribute__((aligned(1024))) char g_lds0[DT_BYTES * NH];
+    __shared__ __attribute__((aligned(1024))) char g_lds1[DT_BYTES * NH];
     __shared__ __attribute__((aligned(16))) float stat[KV_STAT_FLOATS];
 
     const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, h = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform, kept scalar
-    int ktile, bh;                                // triangular steps: low key tiles see most queries: first
-    // one workgroup per (key tile, batch, key/value head); the query head is this launch's
-    // member of the group that shares the key/value head
-    decode_block<false>((int)blockIdx.x, n_tiles, p.B * p.H_kv, ktile, bh);
+    int ktile, bhh;                               // triangular steps: low key tiles see most queries: first
+    // one workgroup per (key tile, batch, key/value head, 128-column half of dK / dV); the query
+    // head is this launch's member of the group that shares the key/value head
+    decode_block<false>((int)blockIdx.x, n_tiles, p.B * p.H_kv * NH, ktile, bhh);
+    const int bh = bhh / NH, ohalf = bhh - bh * NH;
     const int b = bh / p.H_kv, kvh = bh - b * p.H_kv;
     const int hd = kvh * (p.H / p.H_kv) + p.member;
     const int64_t base = b * p.stride_b + hd * p.stride_h;
     const int64_t kv_base = b * p.kv_stride_b + kvh * p.kv_stride_h;
     const int64_t sbase = b * p.stat_stride_b + hd * p.stat_stride_h;
-    const int d = p.d;                                 // d <= 128, zero-padded to 128 columns
+    const int d = p.d;                                 // d <= DP, zero-padded to DP columns
     const int64_t ss = p.kv_stride_s;                  // elements between consecutive rows of K, V, dK, dV
     const int pitch = 2 * (int)p.stride_s;             // bytes between consecutive rows of Q and dO
     const int tile_pitch = DT_ROWS * pitch;            // bytes between 64-row tiles in global memory
@@ -436,16 +474,28 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
     // 8 (r/4) + r%4 >= mask_base - 32 u
     const int mask_base = key_own + p.off - 4 * h;
 
-    uint32_t arow[8], tr0[4], tr1[4], gl[4];
+    uint32_t arow[8], tr0[4], tr1[4], gl[NH][4];
     dt_row_addrs(arow, n, h);
     dt_tr_addrs(tr0, tr1, lane);
-    dt_load_offsets(gl, lane, wave, pitch, d);
+    if (NH > 1) {       // the transposed operands come from this workgroup's half of the columns
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb) {
+            tr0[mb] += ohalf * DT_BYTES;
+            tr1[mb] += ohalf * DT_BYTES;
+        }
+    }
+#pragma unroll
+    for (int hh = 0; hh < NH; ++hh) dt_load_offsets(gl[hh], lane, wave, pitch, d, hh);
+    auto load_tile = [&](dt_rsrc m, int tile_byte_offset, char* buf) {
+#pragma unroll
+        for (int hh = 0; hh < NH; ++hh) dt_load(m, tile_byte_offset, buf + hh * DT_BYTES, gl[hh], wave);
+    };
     // t_first and n_qt are even (k0 and c are multiples of 128): tile t_first goes to buffer 0
     // and there are always at least two tiles
-    dt_load(Qr, t_first * tile_pitch, q_lds0, gl, wave);
-    dt_load(Gr, t_first * tile_pitch, g_lds0, gl, wave);
-    dt_load(Qr, (t_first + 1) * tile_pitch, q_lds1, gl, wave);
-    dt_load(Gr, (t_first + 1) * tile_pitch, g_lds1, gl, wave);
+    load_tile(Qr, t_first * tile_pitch, q_lds0);
+    load_tile(Gr, t_first * tile_pitch, g_lds0);
+    load_tile(Qr, (t_first + 1) * tile_pitch, q_lds1);
+    load_tile(Gr, (t_first + 1) * tile_pitch, g_lds1);
     // statistics of query tile t -> stat[(t & 1)][0 | 1][64]: threads 0..63 LSE * log2(e), 64..127
     // -delta.  The fetch is branch-free (wavefronts 2 and 3 re-read what 0 and 1 read and drop
     // it), so nothing waits for it before the store one trip later.
@@ -470,9 +520,9 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
     stat_store(t_first, stat_fetch());
     stat_store(t_first + 1, stat_fetch());
 
-    bf16x8 kf[8], vf[8];
-    load_b_frags(kf, K + (int64_t)key * ss, h, d);
-    load_b_frags(vf, V + (int64_t)key * ss, h, d);
+    bf16x8 kf[8 * NH], vf[8 * NH];
+    load_b_frags<8 * NH>(kf, K + (int64_t)key * ss, h, d);
+    load_b_frags<8 * NH>(vf, V + (int64_t)key * ss, h, d);
     const float kappa = p.scale * LOG2E;
     f32x16 acck[4], accv[4];
 #pragma unroll
@@ -491,16 +541,18 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
         const char* g0p = g_lds0;
         load_neg_delta(dp_a, stat + DT_ROWS, h);          // tile t_first is in buffer 0
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            bf16x8 qx = dt_read_row(q0p, arow[ks]), gx = dt_read_row(g0p, arow[ks]);
-            if (PART) {
-                qx = zero_beyond_d(qx, ks == part_ks);
-                gx = zero_beyond_d(gx, ks == part_ks);
+        for (int hh = 0; hh < NH; ++hh)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                bf16x8 qx = dt_read_row(q0p + hh * DT_BYTES, arow[ks]), gx = dt_read_row(g0p + hh * DT_BYTES, arow[ks]);
+                if (PART) {
+                    qx = zero_beyond_d(qx, 8 * hh + ks == part_ks);
+                    gx = zero_beyond_d(gx, 8 * hh + ks == part_ks);
+                }
+                if (ks == 0 && hh == 0) mfma_vgpr_first<PART || (DP > 128)>(s_a, qx, kf[0]);
+                else mfma_vgpr_acc<PART || (DP > 128)>(s_a, qx, kf[8 * hh + ks]);
+                mfma_vgpr_acc<PART || (DP > 128)>(dp_a, gx, vf[8 * hh + ks]);
             }
-            if (ks == 0) mfma_vgpr_first<PART>(s_a, qx, kf[0]);
-            else mfma_vgpr_acc<PART>(s_a, qx, kf[ks]);
-            mfma_vgpr_acc<PART>(dp_a, gx, vf[ks]);
-        }
         mfma_results_to_valu(s_a, dp_a);
     }
 
@@ -527,8 +579,8 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
                                   mask_base - 64 * t - 32, part_ks);
             __syncthreads();                     // every wavefront is done with tile t
             if (t + 2 < n_qt) {
-                dt_load(Qr, (t + 2) * tile_pitch, q_cur, gl, wave);
-                dt_load(Gr, (t + 2) * tile_pitch, g_cur, gl, wave);
+                load_tile(Qr, (t + 2) * tile_pitch, q_cur);
+                load_tile(Gr, (t + 2) * tile_pitch, g_cur);
                 rstat = stat_fetch();
             }
         } else {
@@ -566,7 +618,7 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            const int col = 32 * mb + 8 * g + 4 * h;
+            const int col = 128 * ohalf + 32 * mb + 8 * g + 4 * h;
             if (col >= d || !key_ok) continue;            // padding columns, keys beyond the shard
             const int64_t o = (int64_t)key * ss + col;
             float4 x = *reinterpret_cast<float4*>(DV + o);
@@ -590,7 +642,9 @@ bool bwd_mfma_supported(const StepArgs& a, int dtype) {
     const int64_t rows = (int64_t)(a.c + BM - 1) / BM * BM;
     // one workgroup per (128-row tile, batch, head) in a 1-D grid
     if (rows / BM * a.B * a.H >= (int64_t(1) << 31)) return false;
-    return dtype == SA_BF16 && a.d <= D && a.d % 4 == 0 && a.c >= BM &&
+    // head dimensions above 128 (two 128-column halves) in whole 16-byte chunks only
+    if (a.d > 2 * D || (a.d > D && a.d % 8)) return false;
+    return dtype == SA_BF16 && a.d % 4 == 0 && a.c >= BM &&
            rows * 2 * widest + 2 * a.d < (int64_t(1) << 31);
 }
 
@@ -599,7 +653,8 @@ template <int DP, bool PART>
 hipError_t launch_bwd_variant(const StepArgs& a, hipStream_t st) {
     const int n_tiles = (a.c + BM - 1) / BM;
     const bool ragged = a.c % BM != 0;
-    const dim3 grid_q((unsigned)n_tiles * a.B * a.H), grid_kv((unsigned)n_tiles * a.B * a.H_kv), block(256);
+    const dim3 grid_q((unsigned)n_tiles * a.B * a.H), block(256);
+    const dim3 grid_kv((unsigned)n_tiles * a.B * a.H_kv * (DP > 128 ? 2 : 1));
     const bool full = a.kind == MASK_FULL;
     if (ragged) {
         if (full) hipLaunchKernelGGL((bwd_dq_mfma_kernel<true, true, DP, PART>), grid_q, block, 0, st, a, n_tiles);
@@ -628,6 +683,7 @@ hipError_t launch_bwd_variant(const StepArgs& a, hipStream_t st) {
 
 hipError_t launch_bwd_mfma(const StepArgs& a, hipStream_t st) {
     const bool part = a.d % 8 != 0;
+    if (a.d > 128) return launch_bwd_variant<256, false>(a, st);
     if (a.d <= 64) return part ? launch_bwd_variant<64, true>(a, st) : launch_bwd_variant<64, false>(a, st);
     return part ? launch_bwd_variant<128, true>(a, st) : launch_bwd_variant<128, false>(a, st);
 }

@@ -112,23 +112,30 @@ __device__ inline bf16x8 lds_read_tr(const char* lds, uint32_t addr) {
 //   PV: oacc += V(u-1)^T p_prev        v_prev = LDS address of the 32 V rows of sub-tile u-1
 // MASK applies the element mask to s_cur: register r (key 8 (r/4) + 4h + r%4 of the
 // sub-tile) is allowed iff 8 (r/4) + r%4 <= mask_lim (mask_lim already holds -4h).
-// DP: columns computed (128, or 64 for head dimensions up to 64: k-steps 4..7 of the first
-// product and column blocks 2, 3 of the second do not exist then).  PART: d % 8 == 4, the
-// K fragment that holds column d is cleared beyond it (part_ks = its k-step, or -1 for the
-// lanes of the other half-wave).
+// DP: columns computed.  64 for head dimensions up to 64 (k-steps 4..7 of the first product
+// and column blocks 2, 3 of the second do not exist then), 128, or 256 for head dimensions above
+// 128: the K and V tiles then come as two 128-column halves, TILE_BYTES apart in LDS, and every
+// slice holds one MFMA of each product per half.  PART: d % 8 == 4, the K fragment that holds
+// column d is cleared beyond it (part_ks = its k-step, or -1 for the lanes of the other
+// half-wave).
+constexpr int halves_of(int DP) { return DP > 128 ? 2 : 1; }
 template <bool QK, bool SM, bool PV, bool MASK, int DP, bool PART>
 __device__ inline void step(f32x16& s_cur, f32x16& s_next, bf16x8 (&p_cur)[2], bf16x8 (&p_prev)[2],
-                            f32x16 (&oacc)[4], const bf16x8 (&qf)[8], float& m, float& l, float kappa,
-                            const uint32_t (&kaddr)[4], const uint32_t (&vaddr)[4], const char* k_next,
-                            const char* v_prev, int mask_lim, int part_ks) {
-    constexpr int KS = DP / 16, MB = DP / 32;
+                            f32x16 (&oacc)[4 * halves_of(DP)], const bf16x8 (&qf)[8 * halves_of(DP)], float& m,
+                            float& l, float kappa, const uint32_t (&kaddr)[4], const uint32_t (&vaddr)[4],
+                            const char* k_next, const char* v_prev, int mask_lim, int part_ks) {
+    constexpr int NH = halves_of(DP), KS = DP / NH / 16, MB = DP / NH / 32;      // per half
     // Operands of slice i are requested from LDS two slices ahead, so only a few of
-    // them are live at a time; slice i holds QK MFMA i (k-step i) and PV MFMA i
+    // them are live at a time; slice i holds, per half, QK MFMA i (k-step i) and PV MFMA i
     // (16-key group i / 4, 32-column block i % 4).
-    bf16x8 ka[8], va[8];
+    bf16x8 ka[NH][8], va[NH][8];
     auto fetch = [&](int i) {
-        if (QK && i < KS) ka[i] = lds_read_b128(k_next, k_step_addr(kaddr, i));
-        if (PV && i % 4 < MB) va[i] = lds_read_tr(v_prev + (i / 4) * 16 * 256, vaddr[i % 4]);
+#pragma unroll
+        for (int hh = 0; hh < NH; ++hh) {
+            if (QK && i < KS) ka[hh][i] = lds_read_b128(k_next + hh * TILE_BYTES, k_step_addr(kaddr, i));
+            if (PV && i % 4 < MB)
+                va[hh][i] = lds_read_tr(v_prev + hh * TILE_BYTES + (i / 4) * 16 * 256, vaddr[i % 4]);
+        }
     };
     fetch(0);
     fetch(1);
@@ -146,8 +153,13 @@ __device__ inline void step(f32x16& s_cur, f32x16& s_next, bf16x8 (&p_cur)[2], b
     for (int i = 0; i < 8; ++i) {
         __builtin_amdgcn_sched_barrier(0);         // slices stay in program order
         if (i + 2 < 8) fetch(i + 2);
-        if (QK && i < KS) s_next = mfma(PART ? zero_beyond_d(ka[i], i == part_ks) : ka[i], qf[i], s_next);
-        if (PV && i % 4 < MB) oacc[i % 4] = mfma(va[i], p_prev[i / 4], oacc[i % 4]);
+#pragma unroll
+        for (int hh = 0; hh < NH; ++hh) {
+            if (QK && i < KS)
+                s_next = mfma(PART ? zero_beyond_d(ka[hh][i], 8 * hh + i == part_ks) : ka[hh][i], qf[8 * hh + i],
+                              s_next);
+            if (PV && i % 4 < MB) oacc[4 * hh + i % 4] = mfma(va[hh][i], p_prev[i / 4], oacc[4 * hh + i % 4]);
+        }
         if (SM) {
             const float p0 = __builtin_amdgcn_exp2f(fmaf(s_cur[2 * i], kappa, -m));
             const float p1 = __builtin_amdgcn_exp2f(fmaf(s_cur[2 * i + 1], kappa, -m));
@@ -177,7 +189,7 @@ __device__ inline void step(f32x16& s_cur, f32x16& s_next, bf16x8 (&p_cur)[2], b
             m = m_new;
             l *= alpha;
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
+            for (int mb = 0; mb < DP / 32; ++mb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) oacc[mb][r] *= alpha;
             rs = 0.f;
@@ -200,7 +212,7 @@ __device__ inline void step(f32x16& s_cur, f32x16& s_next, bf16x8 (&p_cur)[2], b
 // fp32 angle is off by 0.05 rad) and only then handed to the fp32 sine / cosine instructions,
 // which take revolutions.
 template <int DP>
-__device__ inline void rope_rotate(bf16x8 (&f)[8], const double* turns, int pos, int h) {
+__device__ inline void rope_rotate(bf16x8 (&f)[8 * halves_of(DP)], const double* turns, int pos, int h) {
     constexpr int KS = DP / 16;
 #pragma unroll
     for (int ks = 0; ks < KS / 2; ++ks)
@@ -227,15 +239,15 @@ __device__ inline void rope_rotate(bf16x8 (&f)[8], const double* turns, int pos,
 // triangular and full launches apart; the code is the same.)
 // ROPE: the query rows are rotated by their position ids as they are loaded (d == DP).
 template <bool RAGGED, bool FULL, int DP, bool PART, bool ROPE = false>
-__global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1)
+__global__ void __launch_bounds__(64 * NW, DP > 128 ? 1 : 2)
 fwd_mfma_kernel(StepArgs p, int n_qtiles) {
-    constexpr int KS = DP / 16, MB = DP / 32;
+    constexpr int NH = halves_of(DP), KS = DP / NH / 16, MB = DP / 32;      // k-steps per half, column blocks
     __shared__ double rope_turns[ROPE ? DP / 2 : 1];
-    // one LDS object per tile buffer
-    __shared__ __attribute__((aligned(1024))) char k_lds0[TILE_BYTES];
-    __shared__ __attribute__((aligned(1024))) char k_lds1[TILE_BYTES];
-    __shared__ __attribute__((aligned(1024))) char v_lds0[TILE_BYTES];
-    __shared__ __attribute__((aligned(1024))) char v_lds1[TILE_BYTES];
+    // one LDS object per tile buffer (two 128-column halves each when DP = 256)
+    __shared__ __attribute__((aligned(1024))) char k_lds0[TILE_BYTES * NH];
+    __shared__ __attribute__((aligned(1024))) char k_lds1[TILE_BYTES * NH];
+    __shared__ __attribute__((aligned(1024))) char v_lds0[TILE_BYTES * NH];
+    __shared__ __attribute__((aligned(1024))) char v_lds1[TILE_BYTES * NH];
 
     const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, h = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform, kept scalar
@@ -247,7 +259,7 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     // key/value head of this query head's group (the same head when H_kv == H)
     const int64_t kv_base = b * p.kv_stride_b + (hd / (p.H / p.H_kv)) * p.kv_stride_h;
     const __bf16* Q = (const __bf16*)p.q + base;
-    const int d = p.d;                                 // d <= 128, zero-padded to 128 columns
+    const int d = p.d;                                 // d <= DP, zero-padded to DP columns
     const int64_t ss = p.stride_s;                     // elements between consecutive rows of Q and O
     const int pitch = 2 * (int)p.kv_stride_s;          // bytes between consecutive rows of K and V
     const int tile_pitch = TILE_ROWS * pitch;          // bytes between 64-row tiles in global memory
@@ -280,7 +292,7 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     // per-lane addresses: K A-operand reads per k-step, V transposing reads per 32-column
     // block (bytes within a 32-row half tile), and the global byte offsets of this lane's
     // direct loads
-    uint32_t kaddr[4], vaddr[4], kg0, vg0;
+    uint32_t kaddr[4], vaddr[4], kg0[NH], vg0[NH];
     {
         const int x = n & 15;
 #pragma unroll
@@ -290,22 +302,36 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
         for (int mb = 0; mb < 4; ++mb)
             vaddr[mb] = (4 * h + j4) * 256 + ((4 * (mb ^ j4) + 2 * nh + ((i & 3) >> 1)) << 4) + (i & 1) * 8;
         const int lr = lane >> 4, pc = lane & 15;      // row within the 4-row group, physical chunk
-        kg0 = (4 * wave + lr) * pitch + ((pc ^ (4 * wave + lr)) << 4);     // row 4 wave + lr of each 16
-        // V's swizzle depends on the row within the 4-row group only, so its four pieces
-        // differ by exactly four rows: one lane offset, the rest goes into the scalar offset
-        vg0 = (4 * LPW * wave + lr) * pitch + ((pc ^ (lr << 2)) << 4);
-        // chunks that start at or beyond column d are not fetched: their LDS columns get zeros
-        if (8 * (pc ^ (4 * wave + lr)) >= d) kg0 = DT_OUT_OF_RANGE;
-        if (8 * (pc ^ (lr << 2)) >= d) vg0 = DT_OUT_OF_RANGE;
+#pragma unroll
+        for (int hh = 0; hh < NH; ++hh) {
+            // row 4 wave + lr of each 16; half hh of the rows starts 256 bytes in
+            kg0[hh] = (4 * wave + lr) * pitch + 256 * hh + ((pc ^ (4 * wave + lr)) << 4);
+            // V's swizzle depends on the row within the 4-row group only, so its four pieces
+            // differ by exactly four rows: one lane offset, the rest goes into the scalar offset
+            vg0[hh] = (4 * LPW * wave + lr) * pitch + 256 * hh + ((pc ^ (lr << 2)) << 4);
+            // chunks that start at or beyond column d are not fetched: their LDS columns get zeros
+            if (128 * hh + 8 * (pc ^ (4 * wave + lr)) >= d) kg0[hh] = DT_OUT_OF_RANGE;
+            if (128 * hh + 8 * (pc ^ (lr << 2)) >= d) vg0[hh] = DT_OUT_OF_RANGE;
+        }
     }
 
+    auto load_k = [&](int tile_byte_offset, char* buf) {
+#pragma unroll
+        for (int hh = 0; hh < NH; ++hh)
+            load_tile_direct(K, tile_byte_offset, buf + hh * TILE_BYTES, kg0[hh], wave, pitch);
+    };
+    auto load_v = [&](int tile_byte_offset, char* buf) {
+#pragma unroll
+        for (int hh = 0; hh < NH; ++hh)
+            load_v_tile_direct(V, tile_byte_offset, buf + hh * TILE_BYTES, vg0[hh], wave, pitch);
+    };
     // first tiles on their way while the running state is loaded
-    load_tile_direct(K, 0, k_lds0, kg0, wave, pitch);
-    load_v_tile_direct(V, 0, v_lds0, vg0, wave, pitch);
-    load_tile_direct(K, tile_pitch, k_lds1, kg0, wave, pitch);     // n_kt >= 2 always
+    load_k(0, k_lds0);
+    load_v(0, v_lds0);
+    load_k(tile_pitch, k_lds1);     // n_kt >= 2 always
 
-    bf16x8 qf[8];
-    load_b_frags(qf, Q + (int64_t)a * ss, h, d);
+    bf16x8 qf[8 * NH];
+    load_b_frags<8 * NH>(qf, Q + (int64_t)a * ss, h, d);
     int q_position = 0;
     if (ROPE) {
         q_position = p.q_pos[b * p.pos_stride_b + a];
@@ -314,7 +340,7 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     const float kappa = p.scale * LOG2E;
     float m = L[a] * LOG2E;                   // -inf stays -inf
     float l = (h == 0) ? 1.f : 0.f;           // the two half-waves hold partial row sums
-    f32x16 oacc[4];
+    f32x16 oacc[4 * NH];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
@@ -343,10 +369,12 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) s_a[r] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const bf16x8 ka = lds_read_b128(k_lds0, k_step_addr(kaddr, ks));
-            s_a = mfma(PART ? zero_beyond_d(ka, ks == part_ks) : ka, qf[ks], s_a);
-        }
+        for (int hh = 0; hh < NH; ++hh)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const bf16x8 ka = lds_read_b128(k_lds0 + hh * TILE_BYTES, k_step_addr(kaddr, ks));
+                s_a = mfma(PART ? zero_beyond_d(ka, 8 * hh + ks == part_ks) : ka, qf[8 * hh + ks], s_a);
+            }
     }
 
     // Trip t = iterations u = 2t and 2t+1 with barrier t between them.  Iteration u does
@@ -371,8 +399,8 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
                                                  mask_base - 64 * t, part_ks);
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-        if (LD >= 2) load_tile_direct(K, (t + 2) * tile_pitch, k_cur, kg0, wave, pitch);
-        if (LD >= 1) load_v_tile_direct(V, (t + 1) * tile_pitch, v_prv, vg0, wave, pitch);
+        if (LD >= 2) load_k((t + 2) * tile_pitch, k_cur);
+        if (LD >= 1) load_v((t + 1) * tile_pitch, v_prv);
         step<!LAST, true, true, MASK, DP, PART>(s_b, s_a, p_b, p_a, oacc, qf, m, l, kappa, kaddr, vaddr, k_nxt,
                                                 v_cur, mask_base - 64 * t - 32, part_ks);
     };
@@ -444,7 +472,9 @@ bool fwd_mfma_supported(const StepArgs& a, int dtype) {
     const int64_t rows = (int64_t)(a.c + BM - 1) / BM * BM;
     // one workgroup per (128-row tile, batch, head) in a 1-D grid
     if (rows / BM * a.B * a.H >= (int64_t(1) << 31)) return false;
-    return dtype == SA_BF16 && a.d <= D && a.d % 4 == 0 && a.c >= BM &&
+    // head dimensions above 128 (two 128-column halves) in whole 16-byte chunks only
+    if (a.d > 2 * D || (a.d > D && a.d % 8)) return false;
+    return dtype == SA_BF16 && a.d % 4 == 0 && a.c >= BM &&
            rows * 2 * a.kv_stride_s + 2 * a.d < (int64_t(1) << 31);
 }
 
@@ -467,10 +497,10 @@ void launch_fwd_rope(const StepArgs& a, hipStream_t st, dim3 grid, dim3 block, i
 }
 }  // namespace
 
-// fused query rotation: head dimension 64 or 128 (both halves of a rotation pair in one lane)
-// and block sizes that are a multiple of 128
+// fused query rotation: head dimension 64, 128 or 256 (both halves of a rotation pair in one
+// lane) and block sizes that are a multiple of 128
 bool fwd_mfma_rope_supported(const StepArgs& a, int dtype) {
-    return fwd_mfma_supported(a, dtype) && (a.d == 64 || a.d == 128) && a.c % BM == 0;
+    return fwd_mfma_supported(a, dtype) && (a.d == 64 || a.d == 128 || a.d == 256) && a.c % BM == 0;
 }
 
 hipError_t launch_fwd_mfma(const StepArgs& a, hipStream_t st) {
@@ -479,7 +509,10 @@ hipError_t launch_fwd_mfma(const StepArgs& a, hipStream_t st) {
     const bool part = a.d % 8 != 0;
     if (a.q_pos) {
         if (a.d == 64) launch_fwd_rope<64>(a, st, grid, block, n_qtiles);
-        else launch_fwd_rope<128>(a, st, grid, block, n_qtiles);
+        else if (a.d == 128) launch_fwd_rope<128>(a, st, grid, block, n_qtiles);
+        else launch_fwd_rope<256>(a, st, grid, block, n_qtiles);
+    } else if (a.d > 128) {
+        launch_fwd_variant<256, false>(a, st, grid, block, n_qtiles);
     } else if (a.d <= 64) {
         if (part) launch_fwd_variant<64, true>(a, st, grid, block, n_qtiles);
         else launch_fwd_variant<64, false>(a, st, grid, block, n_qtiles);

@@ -19,7 +19,9 @@ namespace sa {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int TD = 128;          // tile columns: head dimensions up to 128 are zero-padded to it
+constexpr int TD = 128;          // tile columns: head dimensions up to 128 are zero-padded to it;
+                                 // larger ones (up to 256) are held as two such tiles, columns
+                                 // 0..127 and 128..255 of the same rows ("halves")
 constexpr int TR = 64;           // tile rows streamed per iteration
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
@@ -64,13 +66,14 @@ constexpr uint32_t DT_OUT_OF_RANGE = 0x80000000u;     // >= any descriptor range
 
 // byte offsets (within a tile, global side) of the 4 pieces this lane fetches
 // (pitch = bytes between rows in global memory, >= 2 d)
-__device__ inline void dt_load_offsets(uint32_t (&g)[4], int lane, int wave, int pitch, int d) {
+// (half: which 128-column half of the rows this tile holds, 0 unless d > 128)
+__device__ inline void dt_load_offsets(uint32_t (&g)[4], int lane, int wave, int pitch, int d, int half = 0) {
     const int lr = lane >> 4, pc = lane & 15;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int r = 16 * wave + 4 * j + lr;
         const int chunk = pc ^ dt_swz(r);
-        g[j] = 8 * chunk < d ? r * pitch + (chunk << 4) : DT_OUT_OF_RANGE;
+        g[j] = 128 * half + 8 * chunk < d ? r * pitch + 256 * half + (chunk << 4) : DT_OUT_OF_RANGE;
     }
 }
 // PART (d % 8 == 4): fragment of k-step ks read by half h is the chunk 2 ks + h; in the chunk
@@ -193,12 +196,13 @@ __device__ inline void decode_block(int linear, int n_tiles, int n_bh, int& rank
     bh = grp * HEAD_GROUP + (within - rank * heads);
 }
 
-// Row of d <= 128 elements (d a multiple of 4) as B-operand fragments, 8 k-steps of 16,
-// zero-padded to 128 columns.  Nothing beyond the row is read.
-__device__ inline void load_b_frags(bf16x8 (&f)[8], const __bf16* __restrict__ row, int h, int d) {
+// Row of d <= 16 NF elements (d a multiple of 4) as B-operand fragments, NF k-steps of 16,
+// zero-padded to 16 NF columns.  Nothing beyond the row is read.
+template <int NF>
+__device__ inline void load_b_frags(bf16x8 (&f)[NF], const __bf16* __restrict__ row, int h, int d) {
     typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
+    for (int ks = 0; ks < NF; ++ks) {
         const int col = 16 * ks + 8 * h;
         if (col + 8 <= d) {
             f[ks] = *reinterpret_cast<const bf16x8*>(row + col);

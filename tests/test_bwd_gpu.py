@@ -84,3 +84,15 @@ def test_mfma_backward_is_deterministic():
     torch.cuda.synchronize()
     for x, y in zip(a, b):
         assert torch.equal(x, y)
+
+
+@pytest.mark.parametrize("layout", [sa.CONTIGUOUS, sa.STRIPED])
+@pytest.mark.parametrize("B,H,S,d,N", [
+    (1, 2, 768, 256, 3),      # two 128-column halves, c = 256
+    (2, 1, 1024, 256, 2),     # c = 512: tiles before, on and after the diagonal
+    (1, 2, 768, 192, 3),      # second half padded
+    (1, 1, 600, 256, 2),      # c = 300: ragged block
+    (1, 2, 512, 136, 2),      # one chunk into the second half
+])
+def test_mfma_bf16_backward_head_dimension_above_128(layout, B, H, S, d, N):
+    _check(B, H, S, d, N, layout, torch.bfloat16, seed=3000 + d + S, use_driver=True)

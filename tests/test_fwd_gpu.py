@@ -129,6 +129,18 @@ def test_mfma_bf16_padded_head_dimension(layout, d):
 
 
 @pytest.mark.parametrize("layout", [sa.CONTIGUOUS, sa.STRIPED])
+@pytest.mark.parametrize("B,H,S,d,N", [
+    (1, 2, 1024, 256, 4),     # two 128-column halves of K and V per tile
+    (2, 1, 2048, 256, 2),     # c = 1024: unmasked tiles before the diagonal
+    (1, 2, 768, 192, 3),      # second half padded
+    (1, 1, 600, 256, 2),      # c = 300: ragged block
+    (1, 2, 512, 136, 2),      # one chunk into the second half
+])
+def test_mfma_bf16_head_dimension_above_128(layout, B, H, S, d, N):
+    _check_ring(B, H, S, d, N, layout, torch.bfloat16, seed=4000 + d + S, use_driver=True)
+
+
+@pytest.mark.parametrize("layout", [sa.CONTIGUOUS, sa.STRIPED])
 def test_mfma_bf16_scale_and_order(layout):
     pairs = [(j, k) for j in range(4) for k in range(4)]
     np.random.default_rng(2).shuffle(pairs)

@@ -99,7 +99,7 @@ def test_striped_ring_attention_on_rotated_inputs():
 
 
 @pytest.mark.parametrize("layout", [sa.CONTIGUOUS, sa.STRIPED])
-@pytest.mark.parametrize("d", [128, 64])
+@pytest.mark.parametrize("d", [128, 64, 256])
 def test_query_rotation_fused_into_the_forward_step(layout, d):
     # sa_attn_step_fwd_rope rotates the query rows as it loads them; keys are rotated once per
     # shard by sa_rope.  Against the oracle: rotate in fp64, round the rotated queries to bf16
