@@ -302,8 +302,7 @@ __device__ inline void mfma_results_to_valu(f32x16& a, f32x16& b) {
 // an MFMA read of it needs 2 wait states (same table).  The operands normally come straight
 // from LDS reads (ordered by s_waitcnt, no hazard); only the PART instantiations pass them
 // through VALU selects first (zero_beyond_d), and then AFTER_VALU puts the wait in front of
-// the instruction.  The DP = 256 instantiation does the same: it is over the register budget,
-// and the copies the compiler inserts to bring an operand back into a VGPR are VALU writes.
+// the instruction.
 template <bool AFTER_VALU>
 __device__ inline void mfma_vgpr_first(f32x16& acc, bf16x8 a, bf16x8 b) {
     if (AFTER_VALU) asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "v"(b));
@@ -313,6 +312,26 @@ template <bool AFTER_VALU>
 __device__ inline void mfma_vgpr_acc(f32x16& acc, bf16x8 a, bf16x8 b) {
     if (AFTER_VALU) asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
     else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+
+// S / dP product of the dK/dV kernel.  DP <= 128: the asm forms above (results stay in VGPRs).
+// DP = 256: the compiler's own MFMA; K and V alone are 128 registers there, the asm forms would
+// pin them and the score tiles to VGPRs and spill a hundred registers, while the compiler keeps
+// part of them in AGPRs and copies a score tile back when the VALU code wants it (32 copies
+// against 48 MFMAs per step, affordable at this head dimension).
+template <int DP, bool PART>
+__device__ inline void score_mfma(f32x16& acc, bf16x8 a, bf16x8 b, bool first) {
+    if (DP > 128) {
+        if (first) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+        }
+        acc = mfma(a, b, acc);
+    } else if (first) {
+        mfma_vgpr_first<PART>(acc, a, b);
+    } else {
+        mfma_vgpr_acc<PART>(acc, a, b);
+    }
 }
 
 // A workgroup owns 128 key rows (K and V rows in registers as B operands, dK^T and
@@ -394,9 +413,8 @@ __device__ inline void dkdv_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, 
             for (int hh = 0; hh < NH; ++hh) {
                 const bf16x8 qx = PART ? zero_beyond_d(qa[hh][i], 8 * hh + i == part_ks) : qa[hh][i];
                 const bf16x8 gx = PART ? zero_beyond_d(ga[hh][i], 8 * hh + i == part_ks) : ga[hh][i];
-                if (i == 0 && hh == 0) mfma_vgpr_first<PART || (DP > 128)>(s_next, qx, kf[0]);
-                else mfma_vgpr_acc<PART || (DP > 128)>(s_next, qx, kf[8 * hh + i]);
-                mfma_vgpr_acc<PART || (DP > 128)>(dp_next, gx, vf[8 * hh + i]);
+                score_mfma<DP, PART>(s_next, qx, kf[8 * hh + i], i == 0 && hh == 0);
+                score_mfma<DP, PART>(dp_next, gx, vf[8 * hh + i], false);
             }
         }
 #pragma unroll
@@ -549,11 +567,10 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
                     qx = zero_beyond_d(qx, 8 * hh + ks == part_ks);
                     gx = zero_beyond_d(gx, 8 * hh + ks == part_ks);
                 }
-                if (ks == 0 && hh == 0) mfma_vgpr_first<PART || (DP > 128)>(s_a, qx, kf[0]);
-                else mfma_vgpr_acc<PART || (DP > 128)>(s_a, qx, kf[8 * hh + ks]);
-                mfma_vgpr_acc<PART || (DP > 128)>(dp_a, gx, vf[8 * hh + ks]);
+                score_mfma<DP, PART>(s_a, qx, kf[8 * hh + ks], ks == 0 && hh == 0);
+                score_mfma<DP, PART>(dp_a, gx, vf[8 * hh + ks], false);
             }
-        mfma_results_to_valu(s_a, dp_a);
+        if (DP <= 128) mfma_results_to_valu(s_a, dp_a);
     }
 
     float rstat = 0.f;          // statistics of the tile after next, in flight
