@@ -10,7 +10,7 @@ inputs resident in HBM.  The contiguous (Ring Attention) layout is timed beside
 it for the worst-device step latencies the paper's argument is about (Sec. 1:
 a round lasts as long as its slowest device).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3|cfg2|cfg4|cfg5|3b|d64|d256|tiny]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3|cfg1|cfg2|cfg4|cfg5|3b|d64|d256|tiny]
                     [--bwd 0|1] [--cold] [--graph] [--skip-granularity BQxBK] [--kv-heads H_KV]
 
 Prints one JSON line.
@@ -80,6 +80,9 @@ WORKLOADS = {
     "d256": dict(B=1, H=16, d=256, S=262144, N=8, q_dev=7,
                  desc="cfg3's model width with head dimension 256: B1 H16 d256 S262144 N8, bf16, q_dev 7 "
                       "(matrix-core kernels, two 128-column halves)"),
+    "cfg1": dict(B=1, H=1, d=64, S=256, N=4, q_dev=-1, dtype="f32",
+                 desc="Tiny: B1 H1 d64 S256 N4 (64-token shards), fp32, all 16 steps (generic fp32 kernels; "
+                      "launch-bound)"),
     "tiny": dict(B=1, H=2, d=128, S=4096, N=4, q_dev=-1, desc="B1 H2 d128 S4096 N4, bf16 (quick check)"),
 }
 
@@ -105,12 +108,13 @@ class Runner:
         dev = "cuda"
         n_in = 4 if bwd else 3
         hkv = w.get("H_kv", H)           # K and V (inputs 1 and 2) may have fewer heads
-        self.orig = [inputs.gaussian((B, hkv if i in (1, 2) else H, S, d), seed * 16 + i, torch.bfloat16,
+        self.dtype = torch.float32 if w.get("dtype") == "f32" else torch.bfloat16
+        self.orig = [inputs.gaussian((B, hkv if i in (1, 2) else H, S, d), seed * 16 + i, self.dtype,
                                      device=dev) for i in range(n_in)]
         self.perm = [torch.empty_like(x) for x in self.orig]
         self.O = torch.empty(B, H, S, d, dtype=torch.float32, device=dev)
         self.LSE = torch.empty(B, H, S, dtype=torch.float32, device=dev)
-        self.out = torch.empty(B, H, S, d, dtype=torch.bfloat16, device=dev)
+        self.out = torch.empty(B, H, S, d, dtype=self.dtype, device=dev)
         self.c = S // N
         self.shape = sa.shard_shape(self.orig[0], self.c, self.LSE, kv=self.orig[1] if hkv != H else None)
         if bwd:
@@ -216,7 +220,7 @@ def summarize_steps(w, layout, table, per_pair, table_min=None, table_med=None):
             pairs = step_pairs(w, layout, j, k)
             fl = pairs * w["B"] * w["H"] * per_pair * w["d"]
             rows.append(dict(round=i, q_dev=j, kv_dev=k, ms=round(ms, 4),
-                             tflops=round(fl / (ms * 1e9), 1) if ms > 0 else 0.0))
+                             tflops=round(fl / (ms * 1e9), 3) if ms > 0 else 0.0))
             if table_min is not None:
                 rows[-1]["ms_min"] = round(table_min[i][j], 4)
             if table_med is not None:
@@ -302,7 +306,7 @@ def main():
     sa.lib()
     w = dict(WORKLOADS[args.workload])
     if args.steps is None:
-        args.steps = 50 if args.workload in ("cfg2", "tiny") else 10
+        args.steps = 50 if args.workload in ("cfg1", "cfg2", "tiny") else 10
     if args.kv_heads:
         if args.kv_heads < 1 or w["H"] % args.kv_heads:
             ap.error("--kv-heads must divide the workload's %d heads" % w["H"])
@@ -350,13 +354,18 @@ def main():
     traffic = measured_traffic(args.workload) if plain else {}
     c_rows = w["S"] // N
 
+    f32 = w.get("dtype") == "f32"      # the generic kernels: fp32 FMA arithmetic, vector ALU peak
+    peak, bound = (157.3, "alu") if f32 else (PEAK_BF16_TFLOPS, "mfma")
+
     def roof(rows, family, alg_bytes):
         name, kernels = FAMILIES[family]
+        if f32:
+            name = name.replace("_mfma_kernel", "_generic_kernel").replace("bwd_dkdv", "bwd_dkv")
         live = [r for r in rows if r["ms"] > 0]
         tot_ms = sum(r["ms"] for r in live)
         ach = sum(r["tflops"] * r["ms"] for r in live) / max(1e-9, tot_ms)
-        out = dict(bound="mfma", kernel=name, achieved=round(ach, 1), peak=PEAK_BF16_TFLOPS,
-                   unit="TFLOP/s", frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=None,
+        out = dict(bound=bound, kernel=name, achieved=round(ach, 3), peak=peak,
+                   unit="TFLOP/s", frac=round(ach / peak, 4), traffic=None,
                    avg_launch_ms=round(tot_ms / max(1, len(live)), 4), total_ms=round(tot_ms, 3))
         if all(k in traffic for k in kernels):      # bytes per launch (read + written) from the profile
             rd, wr = (sum(traffic[k][i] for k in kernels) for i in (0, 1))
@@ -380,7 +389,7 @@ def main():
         "metric": "useful causal TFLOP/s per ring step (striped layout, worst-loaded device's share)",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "scaling": "weak", "vs_baseline": None, "dtype": w.get("dtype", "bf16"), "data": "synthetic",
         "config": {"workload": args.workload + ": " + w["desc"], "B": w["B"], "H": w["H"],
                    "H_kv": w.get("H_kv", w["H"]), "d": w["d"],
                    "n_seq": w["S"], "N": N, "c": w["S"] // N, "q_dev": w["q_dev"],

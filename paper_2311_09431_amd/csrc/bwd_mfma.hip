@@ -408,22 +408,34 @@ __device__ inline void dkdv_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, 
             fetch_stat(i + AHEAD);
         }
         if (i >= 8 - TAHEAD) fetch_t(i - (8 - TAHEAD));     // the first transposed operands ahead of their use
+        // One wavefront per SIMD: a second MFMA issued right behind the first stalls the
+        // wavefront until the matrix pipeline is free again, and nothing else is issued
+        // meanwhile.  So each MFMA is followed by one score's worth of VALU work, which runs
+        // while it executes.
+        auto score = [&](int r) {
+            const float lr = (r & 1) ? lv[i].y : lv[i].x;
+            float pr = __builtin_amdgcn_exp2f(fmaf(s_cur[r], kappa, -lr));
+            if (MASK && 8 * (r / 4) + (r % 4) < mask_lim) pr = 0.f;
+            pb[r / 8][r % 8] = (__bf16)pr;
+            dsb[r / 8][r % 8] = (__bf16)(pr * dp_cur[r]);
+        };
         if (NEXT && i < KS) {
 #pragma unroll
             for (int hh = 0; hh < NH; ++hh) {
                 const bf16x8 qx = PART ? zero_beyond_d(qa[hh][i], 8 * hh + i == part_ks) : qa[hh][i];
                 const bf16x8 gx = PART ? zero_beyond_d(ga[hh][i], 8 * hh + i == part_ks) : ga[hh][i];
                 score_mfma<DP, PART>(s_next, qx, kf[8 * hh + i], i == 0 && hh == 0);
+                if (hh == 0) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    score(2 * i);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
                 score_mfma<DP, PART>(dp_next, gx, vf[8 * hh + i], false);
             }
-        }
-#pragma unroll
-        for (int r = 2 * i; r < 2 * i + 2; ++r) {
-            const float lr = (r & 1) ? lv[i].y : lv[i].x;
-            float pr = __builtin_amdgcn_exp2f(fmaf(s_cur[r], kappa, -lr));
-            if (MASK && 8 * (r / 4) + (r % 4) < mask_lim) pr = 0.f;
-            pb[r / 8][r % 8] = (__bf16)pr;
-            dsb[r / 8][r % 8] = (__bf16)(pr * dp_cur[r]);
+            score(2 * i + 1);
+        } else {
+            score(2 * i);
+            score(2 * i + 1);
         }
     }
     __builtin_amdgcn_sched_barrier(0);
