@@ -625,7 +625,18 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
     // t_first and n_qt are even (c and k0 are multiples of 128): trips come in pairs and the
     // last one has odd parity
     int t = t_first;
-    if (TRI) {
+    if (TRI && DP > 128) {
+        // One masked form for every trip (beyond the diagonal the mask limit is negative and
+        // removes nothing).  With a second, unmasked copy of the loop this instantiation,
+        // which is over the register budget, kept spilled registers live across its hot loop,
+        // and every reload there waits for the tile loads in flight as well.
+        for (; t + 2 < n_qt; t += 2) {
+            trip(T{}, P0{}, F{}, t);
+            trip(T{}, P1{}, F{}, t + 1);
+        }
+        trip(T{}, P0{}, F{}, t);
+        trip(T{}, P1{}, T{}, t + 1);
+    } else if (TRI) {
         // the trips up to the diagonal carry the element mask: the first two, more under
         // emulated coarse skipping
         for (; t < t_first_fine + 2; t += 2) {
@@ -634,13 +645,15 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
             else trip(T{}, P1{}, T{}, t + 1);
         }
     }
-    for (; t + 2 < n_qt; t += 2) {
-        trip(F{}, P0{}, F{}, t);
-        trip(F{}, P1{}, F{}, t + 1);
-    }
-    if (t < n_qt) {
-        trip(F{}, P0{}, F{}, t);
-        trip(F{}, P1{}, T{}, t + 1);
+    if (!(TRI && DP > 128)) {
+        for (; t + 2 < n_qt; t += 2) {
+            trip(F{}, P0{}, F{}, t);
+            trip(F{}, P1{}, F{}, t + 1);
+        }
+        if (t < n_qt) {
+            trip(F{}, P0{}, F{}, t);
+            trip(F{}, P1{}, T{}, t + 1);
+        }
     }
 
 #pragma unroll
