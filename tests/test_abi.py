@@ -87,6 +87,24 @@ def test_argument_errors_are_reported_before_any_launch():
     # an entirely masked contiguous step is a no-op that succeeds without a launch
     assert f(p, p, p, p, p, 0, 1, 4, sa.CONTIGUOUS, ctypes.byref(ok), None) == 0
 
+    # forward step with the fused query rotation: its own arguments, and only shapes the
+    # matrix-core forward kernel takes (bf16, d = 64 / 128 / 256, c a multiple of 128)
+    fr = L.sa_attn_step_fwd_rope
+    big = dict(dtype=sa.BF16, c=256, d=128, stride_b=2 * 1024 * 128, stride_h=1024 * 128, stat_stride_b=2048,
+               stat_stride_h=1024)
+    good = _shape(**big)
+    assert fr(p, p, p, p, p, null, 0, 10000.0, 0, 0, 4, 0, ctypes.byref(good), None) == -1
+    assert fr(p, p, p, p, p, ctypes.c_void_p(0x1002), 0, 10000.0, 0, 1, 4, 0, ctypes.byref(good), None) == -6
+    assert fr(p, p, p, p, p, p, 0, 1.0, 0, 1, 4, 0, ctypes.byref(good), None) == -2          # base must exceed 1
+    assert fr(p, p, p, p, p, p, 100, 10000.0, 0, 1, 4, 0, ctypes.byref(good), None) == -2      # id rows overlap
+    assert fr(p, p, p, p, p, p, 0, 10000.0, 0, 1, 4, 0, ctypes.byref(ok), None) == -2         # fp32: generic kernels
+    assert fr(p, p, p, p, p, p, 0, 10000.0, 0, 1, 4, 0, ctypes.byref(_shape(**dict(big, d=100, stride_h=1024 * 100,
+              stride_b=2 * 1024 * 100))), None) == -2
+    assert fr(p, p, p, p, p, p, 0, 10000.0, 0, 1, 4, 0, ctypes.byref(_shape(**dict(big, c=192))), None) == -2
+    assert fr(p, p, p, p, p, p, 0, 10000.0, 5, 1, 4, 0, ctypes.byref(good), None) == -3
+    # an entirely masked step with valid arguments: success, nothing launched
+    assert fr(p, p, p, p, p, p, 0, 10000.0, 0, 1, 4, sa.CONTIGUOUS, ctypes.byref(good), None) == 0
+
     g = L.sa_stripe_permute
     assert g(null, p, 1, 16, 4, 4, None) == -1
     assert g(p, p, 1, 16, 4, 4, None) == -5
