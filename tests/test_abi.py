@@ -200,3 +200,9 @@ def test_rope_argument_errors():
     assert f(p, p, p, 3, ctypes.byref(ok), 10000.0, 0, None) == -2      # id rows would overlap
     assert f(p, p, ctypes.c_void_p(0x1002), 0, ctypes.byref(ok), 10000.0, 0, None) == -6
     assert f(p, p, p, 0, ctypes.byref(_shape(d=0)), 10000.0, 0, None) == -2
+
+
+@pytest.mark.gpu
+def test_device_props_are_those_of_an_mi355x():
+    cus, khz, mem = sa.sa_device_props()
+    assert cus == 256 and 1_000_000 <= khz <= 3_000_000 and mem > 200 * 2 ** 30
