@@ -57,8 +57,9 @@ typedef struct {
     int32_t c;             /* rows per device (block size) */
     int32_t d;             /* head dimension: any multiple of 4 up to 256 (Table 1's
                               models have 128 and 100);
-                              bf16 with d <= 128 and c >= 128 takes the MFMA kernels, which
-                              compute 64 columns for d <= 64 and 128 otherwise; the
+                              bf16 with c >= 128 (and d a multiple of 8 when d > 128) takes
+                              the MFMA kernels, which compute 64 columns for d <= 64, 128 for
+                              d <= 128 and 256 above; the
                               columns beyond d are zeros on both sides of every product:
                               nothing that follows a row's d elements in memory is read
                               into a result, and nothing beyond them is written) */
@@ -220,7 +221,7 @@ int sa_ring_bwd(const void* Q, const void* K, const void* V, const void* dO, con
  * if it holds none.  They exist to measure what striping gains at a given granularity, to
  * set beside the paper's tables; skip_bq = skip_bk = 0 selects the kernels' own granularity
  * (32 x 32) and is what the plain entry points do.  Otherwise both must be multiples of 128
- * that divide c, and the shape must be one the MFMA kernels take (bf16, d <= 128,
+ * that divide c, and the shape must be one the MFMA kernels take (bf16, see sa_shape.d,
  * c % 128 == 0); anything else returns SA_ERR_SHAPE.  All other arguments as in the plain
  * entry points.
  */

@@ -1,5 +1,5 @@
 // Backward ring step on the CDNA4 matrix cores (bf16 operands, fp32 accumulate),
-// head dimension up to 128 (zero-padded to 128 columns).  The paper describes no
+// head dimension up to 256 (64, 128 or 256 columns computed).  The paper describes no
 // backward pass; this is the analytic gradient of causal attention (Sec. 2.1) restricted to the pairs that
 // GetMask(j, k) allows, with P recomputed from the saved log-sum-exp:
 //   P = exp(scale q.k - LSE),  dV += P^T dO,  dP = dO V^T,

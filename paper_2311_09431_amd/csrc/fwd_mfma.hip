@@ -1,5 +1,5 @@
 // Forward ring step on the CDNA4 matrix cores (bf16 operands, fp32 accumulate),
-// head dimension up to 128 (zero-padded to 128 columns): AccumulateAttentionFragment
+// head dimension up to 256 (64, 128 or 256 columns computed): AccumulateAttentionFragment
 // of Algorithm 1 with the fused log-sum-exp merge, skipping every 32-key sub-tile
 // that GetMask(j, k) masks entirely for a 32-query wavefront (Sec. 2.2.1); a coarser
 // skipping granularity (Sec. 3.1) can be emulated on request.
