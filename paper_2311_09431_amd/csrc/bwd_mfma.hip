@@ -570,10 +570,12 @@ bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
         const char* q0p = q_lds0;
         const char* g0p = g_lds0;
         load_neg_delta(dp_a, stat + DT_ROWS, h);          // tile t_first is in buffer 0
+        // same order of the partial products as in dkdv_step (k-step outside, half inside): a
+        // sub-tile's scores have the same bits whether this prologue or a step computes them
 #pragma unroll
-        for (int hh = 0; hh < NH; ++hh)
+        for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
+            for (int hh = 0; hh < NH; ++hh) {
                 bf16x8 qx = dt_read_row(q0p + hh * DT_BYTES, arow[ks]), gx = dt_read_row(g0p + hh * DT_BYTES, arow[ks]);
                 if (PART) {
                     qx = zero_beyond_d(qx, 8 * hh + ks == part_ks);

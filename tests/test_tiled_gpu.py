@@ -41,7 +41,8 @@ def _ring_fwd(Qp, Kp, Vp, N, layout, c, bq, bk):
 @pytest.mark.parametrize("layout", [sa.CONTIGUOUS, sa.STRIPED])
 @pytest.mark.parametrize("S,N,bq,bk", CASES)
 def test_tiled_ring_gives_the_same_bits(layout, S, N, bq, bk):
-    B, H, d = 1, 2, (100 if bq == 256 else 128)       # both the padded and the full head dimension
+    # the padded, the 64-column, the two-half and the full head dimension
+    B, H, d = 1, 2, {256: 100, 1024: 64, 512: 256}.get(bq, 128)
     c = S // N
     Q, K, V, dO = (x.cuda() for x in inputs.qkv(B, H, S, d, S + bq + bk, torch.bfloat16, with_dout=True))
     Qp, Kp, Vp, dOp = (hp.to_device_order(x, N, layout) for x in (Q, K, V, dO))
