@@ -2,7 +2,12 @@
 (every sub-tile of a coarse tile that holds an allowed pair) but must give the SAME bits as
 the plain entry points, because masked elements contribute exact zeros; and the plain entry
 points are checked against the oracle elsewhere.  One case is also set beside the oracle
-directly."""
+directly.
+
+The comparison is also a guard for the hand-ordered matrix-core code: under coarse tiling the
+sub-tiles at the diagonal, which the plain call computes in a kernel's prologue, are computed
+inside its pipelined loop instead (other neighbours, other wait distances), so a score tile
+read before its product has landed in either place shows as different bits."""
 import numpy as np
 import pytest
 import torch
