@@ -1,5 +1,5 @@
 // Backward ring step on the CDNA4 matrix cores (bf16 operands, fp32 accumulate),
-// head dimension up to 256 (64, 128 or 256 columns computed).  The paper describes no
+// head dimension up to 256 (64, 112, 128 or 256 columns computed).  The paper describes no
 // backward pass; this is the analytic gradient of causal attention (Sec. 2.1) restricted to the pairs that
 // GetMask(j, k) allows, with P recomputed from the saved log-sum-exp:
 //   P = exp(scale q.k - LSE),  dV += P^T dO,  dP = dO V^T,
@@ -52,12 +52,11 @@ __device__ inline bf16x8 pack8(const f32x16& x, int first) {
 // visible, one releases the tile just finished for the next request.
 
 // DP: columns computed.  64 for head dimensions up to 64 (k-steps 4..7 of the S and dP
-// products and column blocks 2, 3 of the dQ product do not exist then), 128, or 256 for head
-// dimensions above 128: the K and V tiles then come as two 128-column halves, DT_BYTES apart in
+// products and column blocks 2, 3 of the dQ product do not exist then), 112 for those up to 112
+// (no k-step 7), 128, or 256 for head dimensions above 128: the K and V tiles then come as two 128-column halves, DT_BYTES apart in
 // LDS, and every slice holds one MFMA of each product per half.  PART: d % 8 == 4, the K and V
 // fragments that hold column d are cleared beyond it (part_ks = the k-step, or -1 for the lanes
 // of the other half-wave).
-constexpr int halves_of(int DP) { return DP > 128 ? 2 : 1; }
 template <bool NEXT, bool MASK, int DP, bool PART>
 __device__ inline void dq_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, f32x16& dp_next,
                                f32x16 (&acc)[4 * halves_of(DP)], const bf16x8 (&qf)[8 * halves_of(DP)],
@@ -65,7 +64,7 @@ __device__ inline void dq_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, f3
                                const uint32_t (&arow)[8], const uint32_t (&tr0)[4], const uint32_t (&tr1)[4],
                                const char* k_next, const char* v_next, const char* k_cur, int mask_lim,
                                int part_ks) {
-    constexpr int NH = halves_of(DP), KS = DP / NH / 16, MB = DP / NH / 32;      // per half
+    constexpr int NH = halves_of(DP), KS = ksteps_of(DP), MB = blocks_of(DP);      // per half
     bf16x8 ka[NH][8], va[NH][8], kt[NH][8], dsb[2];
     auto fetch = [&](int i) {
         if (NEXT && i < KS) {
@@ -131,7 +130,7 @@ __device__ inline void dq_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, f3
 template <bool RAGGED, bool FULL, int DP, bool PART>
 __global__ void __launch_bounds__(256, DP > 128 ? 1 : 2)
 bwd_dq_mfma_kernel(StepArgs p, int n_tiles) {
-    constexpr int NH = halves_of(DP), KS = DP / NH / 16, MB = DP / 32;      // k-steps per half, column blocks
+    constexpr int NH = halves_of(DP), KS = ksteps_of(DP), MB = halves_of(DP) * blocks_of(DP);      // k-steps per half, column blocks
     // one LDS object per tile buffer (two 128-column halves each when DP = 256)
     __shared__ __attribute__((aligned(1024))) char k_lds0[DT_BYTES * NH];
     __shared__ __attribute__((aligned(1024))) char k_lds1[DT_BYTES * NH];
@@ -369,7 +368,7 @@ __device__ inline void dkdv_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, 
                                  const char* g_next, const char* q_cur, const char* g_cur,
                                  const float* stat_cur, const float* stat_next, int h, int mask_lim,
                                  int part_ks) {
-    constexpr int NH = halves_of(DP), KS = DP / NH / 16, MB = DP / NH / 32;      // per half
+    constexpr int NH = halves_of(DP), KS = ksteps_of(DP), MB = blocks_of(DP);      // per half
     bf16x8 qa[NH][8], ga[NH][8], qt[8], gt[8], pb[2], dsb[2];
     if (NEXT) load_neg_delta(dp_next, stat_next + DT_ROWS, h);
     auto fetch = [&](int i) {
@@ -456,7 +455,7 @@ __device__ inline void dkdv_step(f32x16& s_cur, f32x16& dp_cur, f32x16& s_next, 
 template <bool TRI, bool RAGGED, int DP, bool PART>
 __global__ void __launch_bounds__(256, 1)
 bwd_dkdv_mfma_kernel(StepArgs p, int n_tiles) {
-    constexpr int NH = halves_of(DP), KS = DP / NH / 16, MB = DP / NH / 32;      // per half
+    constexpr int NH = halves_of(DP), KS = ksteps_of(DP), MB = blocks_of(DP);      // per half
     // one LDS object per tile buffer (two 128-column halves each when DP = 256)
     __shared__ __attribute__((aligned(1024))) char q_lds0[DT_BYTES * NH];
     __shared__ __attribute__((aligned(1024))) char q_lds1[DT_BYTES * NH];
@@ -729,6 +728,7 @@ hipError_t launch_bwd_mfma(const StepArgs& a, hipStream_t st) {
     const bool part = a.d % 8 != 0;
     if (a.d > 128) return launch_bwd_variant<256, false>(a, st);
     if (a.d <= 64) return part ? launch_bwd_variant<64, true>(a, st) : launch_bwd_variant<64, false>(a, st);
+    if (a.d <= 112) return part ? launch_bwd_variant<112, true>(a, st) : launch_bwd_variant<112, false>(a, st);
     return part ? launch_bwd_variant<128, true>(a, st) : launch_bwd_variant<128, false>(a, st);
 }
 

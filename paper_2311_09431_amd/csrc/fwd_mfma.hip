@@ -1,5 +1,5 @@
 // Forward ring step on the CDNA4 matrix cores (bf16 operands, fp32 accumulate),
-// head dimension up to 256 (64, 128 or 256 columns computed): AccumulateAttentionFragment
+// head dimension up to 256 (64, 112, 128 or 256 columns computed): AccumulateAttentionFragment
 // of Algorithm 1 with the fused log-sum-exp merge, skipping every 32-key sub-tile
 // that GetMask(j, k) masks entirely for a 32-query wavefront (Sec. 2.2.1); a coarser
 // skipping granularity (Sec. 3.1) can be emulated on request.
@@ -113,18 +113,17 @@ __device__ inline bf16x8 lds_read_tr(const char* lds, uint32_t addr) {
 // MASK applies the element mask to s_cur: register r (key 8 (r/4) + 4h + r%4 of the
 // sub-tile) is allowed iff 8 (r/4) + r%4 <= mask_lim (mask_lim already holds -4h).
 // DP: columns computed.  64 for head dimensions up to 64 (k-steps 4..7 of the first product
-// and column blocks 2, 3 of the second do not exist then), 128, or 256 for head dimensions above
-// 128: the K and V tiles then come as two 128-column halves, TILE_BYTES apart in LDS, and every
-// slice holds one MFMA of each product per half.  PART: d % 8 == 4, the K fragment that holds
+// and column blocks 2, 3 of the second do not exist then), 112 for those up to 112 (no k-step
+// 7), 128, or 256 for head dimensions above 128: the K and V tiles then come as two 128-column
+// halves, TILE_BYTES apart in LDS, and every slice holds one MFMA of each product per half.  PART: d % 8 == 4, the K fragment that holds
 // column d is cleared beyond it (part_ks = its k-step, or -1 for the lanes of the other
 // half-wave).
-constexpr int halves_of(int DP) { return DP > 128 ? 2 : 1; }
 template <bool QK, bool SM, bool PV, bool MASK, int DP, bool PART>
 __device__ inline void step(f32x16& s_cur, f32x16& s_next, bf16x8 (&p_cur)[2], bf16x8 (&p_prev)[2],
                             f32x16 (&oacc)[4 * halves_of(DP)], const bf16x8 (&qf)[8 * halves_of(DP)], float& m,
                             float& l, float kappa, const uint32_t (&kaddr)[4], const uint32_t (&vaddr)[4],
                             const char* k_next, const char* v_prev, int mask_lim, int part_ks) {
-    constexpr int NH = halves_of(DP), KS = DP / NH / 16, MB = DP / NH / 32;      // per half
+    constexpr int NH = halves_of(DP), KS = ksteps_of(DP), MB = blocks_of(DP);      // per half
     // Operands of slice i are requested from LDS two slices ahead, so only a few of
     // them are live at a time; slice i holds, per half, QK MFMA i (k-step i) and PV MFMA i
     // (16-key group i / 4, 32-column block i % 4).
@@ -189,7 +188,7 @@ __device__ inline void step(f32x16& s_cur, f32x16& s_next, bf16x8 (&p_cur)[2], b
             m = m_new;
             l *= alpha;
 #pragma unroll
-            for (int mb = 0; mb < DP / 32; ++mb)
+            for (int mb = 0; mb < halves_of(DP) * blocks_of(DP); ++mb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) oacc[mb][r] *= alpha;
             rs = 0.f;
@@ -241,7 +240,7 @@ __device__ inline void rope_rotate(bf16x8 (&f)[8 * halves_of(DP)], const double*
 template <bool RAGGED, bool FULL, int DP, bool PART, bool ROPE = false>
 __global__ void __launch_bounds__(64 * NW, DP > 128 ? 1 : 2)
 fwd_mfma_kernel(StepArgs p, int n_qtiles) {
-    constexpr int NH = halves_of(DP), KS = DP / NH / 16, MB = DP / 32;      // k-steps per half, column blocks
+    constexpr int NH = halves_of(DP), KS = ksteps_of(DP), MB = halves_of(DP) * blocks_of(DP);      // k-steps per half, column blocks
     __shared__ double rope_turns[ROPE ? DP / 2 : 1];
     // one LDS object per tile buffer (two 128-column halves each when DP = 256)
     __shared__ __attribute__((aligned(1024))) char k_lds0[TILE_BYTES * NH];
@@ -516,6 +515,9 @@ hipError_t launch_fwd_mfma(const StepArgs& a, hipStream_t st) {
     } else if (a.d <= 64) {
         if (part) launch_fwd_variant<64, true>(a, st, grid, block, n_qtiles);
         else launch_fwd_variant<64, false>(a, st, grid, block, n_qtiles);
+    } else if (a.d <= 112) {
+        if (part) launch_fwd_variant<112, true>(a, st, grid, block, n_qtiles);
+        else launch_fwd_variant<112, false>(a, st, grid, block, n_qtiles);
     } else {
         if (part) launch_fwd_variant<128, true>(a, st, grid, block, n_qtiles);
         else launch_fwd_variant<128, false>(a, st, grid, block, n_qtiles);

@@ -23,6 +23,16 @@ constexpr int TD = 128;          // tile columns: head dimensions up to 128 are 
                                  // larger ones (up to 256) are held as two such tiles, columns
                                  // 0..127 and 128..255 of the same rows ("halves")
 constexpr int TR = 64;           // tile rows streamed per iteration
+
+// DP, the number of columns a kernel instantiation computes: 64, 112, 128 or 256.  Tiles are
+// always 128 columns wide (two of them, "halves", for 256); a smaller DP only leaves out work:
+// a contraction over the head dimension takes ksteps_of(DP) steps of 16 columns per half, a
+// product whose output has head-dimension columns blocks_of(DP) blocks of 32 per half.
+// 112 (head dimensions 65..112, e.g. the 100 of the paper's 3B model, Table 1) drops the last
+// k-step and keeps all four output blocks.
+constexpr int halves_of(int DP) { return DP > 128 ? 2 : 1; }
+constexpr int ksteps_of(int DP) { return (DP / halves_of(DP) + 15) / 16; }
+constexpr int blocks_of(int DP) { return (DP / halves_of(DP) + 31) / 32; }
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 

@@ -71,7 +71,7 @@ def test_mfma_bf16_backward(layout, B, H, S, N):
 
 
 @pytest.mark.parametrize("layout", [sa.CONTIGUOUS, sa.STRIPED])
-@pytest.mark.parametrize("d", [100, 64, 72, 4, 124])
+@pytest.mark.parametrize("d", [100, 64, 72, 4, 124, 112, 116])
 def test_mfma_bf16_backward_padded_head_dimension(layout, d):
     _check(1, 2, 768, d, 3, layout, torch.bfloat16, seed=2000 + d, use_driver=True)
 

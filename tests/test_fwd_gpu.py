@@ -120,11 +120,12 @@ def test_mfma_bf16_ring(layout, B, H, S, N):
 
 
 @pytest.mark.parametrize("layout", [sa.CONTIGUOUS, sa.STRIPED])
-@pytest.mark.parametrize("d", [100, 64, 72, 4, 124])
+@pytest.mark.parametrize("d", [100, 64, 72, 4, 124, 112, 116])
 def test_mfma_bf16_padded_head_dimension(layout, d):
-    # d < 128 runs on the matrix-core kernel zero-padded to 128 columns; 100 is the head
-    # dimension of Table 1's 3B model (half a 16-byte chunk at the row end), 72 ends on a
-    # chunk, 124 leaves one group of four, 4 is the smallest
+    # d < 128 runs on the matrix-core kernel that computes 64, 112 or 128 columns; 100 is the
+    # head dimension of Table 1's 3B model (half a 16-byte chunk at the row end), 72 ends on a
+    # chunk, 124 leaves one group of four, 4 is the smallest, 112 is the widest that skips the
+    # last 16-column step of the contractions over d and 116 the narrowest that does not
     _check_ring(1, 2, 1024, d, 4, layout, torch.bfloat16, seed=1000 + d, use_driver=True)
 
 

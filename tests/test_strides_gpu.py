@@ -100,7 +100,7 @@ def test_rows_that_overlap_are_rejected():
 @pytest.mark.parametrize("d,pitch", [(100, 128), (64, 128), (36, 40), (124, 136), (192, 256), (136, 144)])
 def test_gap_between_rows_may_hold_anything(layout, d, pitch):
     # Rows of d elements at a pitch of more than d, the gap filled with NaN (what an
-    # uninitialised buffer may hold): the matrix-core kernels compute 64, 128 or 256 columns
+    # uninitialised buffer may hold): the matrix-core kernels compute 64, 112, 128 or 256 columns
     # and must neither read the gap into a product nor write into it.
     B, H, S, N = 1, 2, 768, 3
     c = S // N
