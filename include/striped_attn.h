@@ -58,8 +58,8 @@ typedef struct {
     int32_t d;             /* head dimension: any multiple of 4 up to 256 (Table 1's
                               models have 128 and 100);
                               bf16 with c >= 128 (and d a multiple of 8 when d > 128) takes
-                              the MFMA kernels, which compute 64 columns for d <= 64, 128 for
-                              d <= 128 and 256 above; the
+                              the MFMA kernels, which compute 64 columns for d <= 64, 112 for
+                              d <= 112, 128 for d <= 128 and 256 above; the
                               columns beyond d are zeros on both sides of every product:
                               nothing that follows a row's d elements in memory is read
                               into a result, and nothing beyond them is written) */
