@@ -5,31 +5,42 @@
 
 namespace sa {
 
-// One thread moves one VEC-byte chunk; a row of `chunks` chunks is read and written
-// contiguously (256-byte rows = 16 lanes x 16 B), only the row start jumps.  Threads are laid
-// out over the side whose rows are INTERLEAVED (the original order): rows r and r + N of it
-// are neighbours on the other side, so N-row groups of consecutive threads touch N runs of
-// consecutive rows there, and the interleaved side itself is walked front to back.
-//   forward: thread row t of the source      -> dst row (t mod N) * c + t div N
-//   inverse: thread row t of the destination <- src row (t mod N) * c + t div N
-// (Walking the permuted side instead makes every 256-byte read of the forward direction a
-// separate piece N rows apart: 4.86 TB/s against 5.04 TB/s this way on 2 GiB tensors, where a
-// plain device-to-device copy of the same size runs at 4.93 TB/s.)
-template <typename VecT>
+// One thread moves one VEC-byte chunk at a time; a row of `chunks` chunks is read and written
+// contiguously (256-byte rows = 16 lanes x 16 B), only the row start jumps.  A block is laid
+// out as (rows, lanes per row) with a power-of-two number of lanes per row, blockIdx.y walks the
+// outer index, so the only division a thread does is one in 32 bits (n_seq < 2^31; longer
+// sequences take 64-bit arithmetic).
+//
+// The threads walk the rows of one side front to back ("here") and jump on the other:
+//   other(t) = (t mod div) * mul + t div div
+//   stripe,   walking the source:       scatter dst[other(t)] = src[t],  div = N, mul = c
+//   stripe,   walking the destination:  gather  dst[t] = src[other(t)],  div = c, mul = N
+//   unstripe, walking the destination:  gather  dst[t] = src[other(t)],  div = N, mul = c
+// Walking the side in the ORIGINAL token order means rows t and t + N are neighbours on the
+// other side, so N-row groups of consecutive rows touch N runs of consecutive rows there.  For
+// rows that are a whole number of 128-byte lines that is the fastest form in both directions
+// (2 GiB tensors of 256-byte rows: stripe 5.05-5.2 TB/s scattering, 4.86 gathering; a plain
+// device-to-device copy of the same size runs at 4.93 TB/s).  Rows that end inside a line
+// (200 bytes: head dimension 100) are only written contiguously: scattered, their partial
+// lines reach memory before the neighbouring row has filled them (3.05 TB/s against 4.8).
+template <typename VecT, typename IdxT>
 __global__ void __launch_bounds__(256)
-permute_kernel(const VecT* __restrict__ src, VecT* __restrict__ dst, int64_t n_seq, int64_t chunks,
-               int N, int64_t c, bool inverse, int64_t total) {
-    int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t step = (int64_t)gridDim.x * blockDim.x;
-    for (; idx < total; idx += step) {
-        const int64_t x = idx % chunks;
-        const int64_t row = idx / chunks;      // o * n_seq + t
-        const int64_t o = row / n_seq;
-        const int64_t t = row - o * n_seq;
-        const int64_t a = t / N, dev = t - a * N;
-        const int64_t other = (o * n_seq + dev * c + a) * chunks + x;
-        if (!inverse) dst[other] = src[idx];
-        else dst[idx] = src[other];
+permute_kernel(const VecT* __restrict__ src, VecT* __restrict__ dst, int64_t outer, int64_t n_seq,
+               int64_t chunks, int64_t div, int64_t mul, bool gather, int lpr_log2) {
+    const int lpr = 1 << lpr_log2;                       // lanes per row
+    const int x0 = threadIdx.x & (lpr - 1), r = threadIdx.x >> lpr_log2;
+    const int64_t rows_per_block = 256 >> lpr_log2;
+    for (int64_t o = blockIdx.y; o < outer; o += gridDim.y) {
+        const VecT* s = src + o * n_seq * chunks;
+        VecT* d = dst + o * n_seq * chunks;
+        for (int64_t t = blockIdx.x * rows_per_block + r; t < n_seq; t += gridDim.x * rows_per_block) {
+            const IdxT q = (IdxT)t / (IdxT)div, rem = (IdxT)t - q * (IdxT)div;
+            const int64_t here = t * chunks, other = ((int64_t)rem * mul + (int64_t)q) * chunks;
+            for (int64_t x = x0; x < chunks; x += lpr) {
+                if (gather) d[here + x] = s[other + x];
+                else d[other + x] = s[here + x];
+            }
+        }
     }
 }
 
@@ -37,11 +48,25 @@ template <typename VecT>
 static hipError_t run(const void* src, void* dst, int64_t outer, int64_t n_seq, int64_t inner_bytes,
                       int N, bool inverse, hipStream_t st) {
     const int64_t chunks = inner_bytes / (int64_t)sizeof(VecT);
-    const int64_t total = outer * n_seq * chunks;
-    int64_t blocks = (total + 255) / 256;
-    if (blocks > 256 * 64) blocks = 256 * 64;   // grid-stride beyond 64 blocks per CU
-    hipLaunchKernelGGL(permute_kernel<VecT>, dim3((unsigned)blocks), dim3(256), 0, st,
-                       (const VecT*)src, (VecT*)dst, n_seq, chunks, N, n_seq / N, inverse, total);
+    int lpr_log2 = 0;
+    while (lpr_log2 < 8 && (int64_t(1) << lpr_log2) < chunks) ++lpr_log2;
+    const int64_t rows_per_block = 256 >> lpr_log2;
+    // about 64 blocks per CU over both grid dimensions, grid-stride beyond
+    const int64_t gy = outer < 65535 ? outer : 65535;
+    int64_t gx = (n_seq + rows_per_block - 1) / rows_per_block;
+    const int64_t cap = (256 * 64 + gy - 1) / gy;
+    if (gx > cap) gx = cap;
+    const dim3 grid((unsigned)gx, (unsigned)gy), block(256);
+    const int64_t c = n_seq / N;
+    const bool gather = inverse || inner_bytes % 128 != 0;
+    const bool walk_original = inverse || !gather;      // else: stripe walking its destination
+    const int64_t div = walk_original ? N : c, mul = walk_original ? c : N;
+    if (n_seq < (int64_t(1) << 31))
+        hipLaunchKernelGGL((permute_kernel<VecT, uint32_t>), grid, block, 0, st, (const VecT*)src, (VecT*)dst,
+                           outer, n_seq, chunks, div, mul, gather, lpr_log2);
+    else
+        hipLaunchKernelGGL((permute_kernel<VecT, int64_t>), grid, block, 0, st, (const VecT*)src, (VecT*)dst,
+                           outer, n_seq, chunks, div, mul, gather, lpr_log2);
     return hipGetLastError();
 }
 
