@@ -44,10 +44,12 @@ def _head_f64(x, h):
     return x[0, h].to("cpu").to(torch.float64).numpy()
 
 
+@pytest.mark.parametrize("d", [128, 100])
 @pytest.mark.parametrize("layout", [sa.STRIPED, sa.CONTIGUOUS])
-def test_one_devices_share_at_256k_forward(layout):
-    # seq 262144, N = 8 (32768-token shards), 32 heads, d = 128, bf16: all 8 steps of q_dev 7
-    B, H, S, d, N, q_dev = 1, 32, 262144, 128, 8, 7
+def test_one_devices_share_at_256k_forward(layout, d):
+    # seq 262144, N = 8 (32768-token shards), 32 heads, bf16: all 8 steps of q_dev 7, at the head
+    # dimension of Table 1's 1B / 7B models (128) and of its 3B model (100)
+    B, H, S, N, q_dev = 1, 32, 262144, 8, 7
     c = S // N
     Q, K, V = inputs.qkv(B, H, S, d, 3, torch.bfloat16, device="cuda")
     Qp, Kp, Vp = _device_order([Q, K, V], N, layout)
@@ -203,15 +205,16 @@ def _index_in_device_order(pos, N, c, layout):
     return (pos % N) * c + pos // N if layout == sa.STRIPED else pos
 
 
-def test_dense_backward_at_256k_shards():
+@pytest.mark.parametrize("d", [128, 100])
+def test_dense_backward_at_256k_shards(d):
     # The shape bench.py times (32 heads, d = 128, 32768-token shards of a 262144-token
-    # sequence, the large-grid workgroup order) with a DENSE dO, whole ring and one device's
-    # share, both layouts.  Against the oracle: dQ on sampled rows (dQ_i needs row i of dO
+    # sequence, the large-grid workgroup order; and the same at the 3B model's d = 100, the
+    # `3b` workload) with a DENSE dO, whole ring and one device's share, both layouts.  Against the oracle: dQ on sampled rows (dQ_i needs row i of dO
     # only) and dK, dV on the keys of the last 512 positions (only the queries at or after a
     # key see it).  Properties that hold for every row: sum_j dV_j = sum_i dO_i and
     # <Q, dQ> = <K, dK> per head, and striped == contiguous after un-permuting (two different
     # tile walks of the same sum).
-    B, H, S, d, N, q_dev = 1, 32, 262144, 128, 8, 7
+    B, H, S, N, q_dev = 1, 32, 262144, 8, 7
     c = S // N
     Q, K, V, dO = inputs.qkv(B, H, S, d, 3, torch.bfloat16, device="cuda", with_dout=True)
     scale = 1.0 / np.sqrt(d)
