@@ -1,6 +1,6 @@
 """Summarise rocprofv3 CSV output of a bench.py run into the text kept under profiles/.
 
-    python -m paper_2311_09431_amd.profsum [--kt DIR] [--fetch DIR] [--write DIR] [--sq DIR] [--prefix P]
+    python -m paper_2311_09431_amd.profsum [--kt DIR] [--fetch DIR] [--write DIR] [--sq DIR] [--sq2 DIR] [--prefix P]
 
 Each DIR is the `-d` folder of one rocprofv3 run of `python bench.py ...` made with
 `--output-format csv -o P`:
@@ -8,6 +8,9 @@ Each DIR is the `-d` folder of one rocprofv3 run of `python bench.py ...` made w
   --fetch  `--pmc FETCH_SIZE`                     (P_counter_collection.csv)
   --write  `--pmc WRITE_SIZE`
   --sq     `--pmc SQ_... GRBM_GUI_ACTIVE`         (any counters; listed per kernel)
+  --sq2    a second counter pass of the same kind (one run holds at most 8 SQ counters)
+With --kt and --sq it also prints one DERIVED line per matrix-core kernel: clock, matrix-core
+busy share, instructions per MFMA and (with --sq2) the wait shares of a wavefront's cycles.
 Prints the per-kernel tables and, when both byte counters are there, one line per library
 kernel that bench.py parses:
     TRAFFIC <kernel> read_GB=<x> written_GB=<y>
@@ -89,9 +92,48 @@ def traffic_lines(fetch, write):
     return out
 
 
+# MI355X: 8 XCDs (GRBM_GUI_ACTIVE is summed over them), 256 CUs x 4 SIMDs; one
+# v_mfma_f32_32x32x16_bf16 is 2 x 32 x 32 x 16 flop
+_XCDS, _SIMDS, _MFMA_FLOP = 8, 1024, 32768
+
+
+def derived_lines(kt_dir, prefix, sq, sq2):
+    avg_ns = {_short(r["Name"]): float(r["AverageNs"]) for r in
+              csv.DictReader(open(_find(kt_dir, prefix, "_kernel_stats.csv")))}
+    mean = lambda v, c: sum(v[c]) / len(v[c]) if c in v else None
+    out = ["", "derived per matrix-core kernel (kernel-trace average duration; clock = GRBM_GUI_ACTIVE / %d XCDs / "
+               "duration; busy = SQ_VALU_MFMA_BUSY_CYCLES / (%d SIMDs x GRBM_GUI_ACTIVE / %d); executed = "
+               "SQ_INSTS_MFMA x %d flop / duration; waits = share of SQ_WAVE_CYCLES)" % (_XCDS, _SIMDS, _XCDS, _MFMA_FLOP)]
+    for k, v in sq.items():
+        n_mfma, grbm = mean(v, "SQ_INSTS_MFMA"), mean(v, "GRBM_GUI_ACTIVE")
+        if not n_mfma or not grbm or k not in avg_ns:
+            continue
+        ns = avg_ns[k]
+        line = "DERIVED %-66s avg_ms=%7.3f executed_TFLOPs=%6.0f clock_GHz=%.2f" % (
+            (re.search(r"\w+<[^>]*>", k) or re.search(r".*", k)).group(0)[:66], ns / 1e6, n_mfma * _MFMA_FLOP / ns / 1e3, grbm / _XCDS / ns)
+        busy, coex = mean(v, "SQ_VALU_MFMA_BUSY_CYCLES"), mean(v, "SQ_VALU_MFMA_COEXEC_CYCLES")
+        if busy:
+            line += " mfma_busy=%.0f%%" % (100 * busy / (_SIMDS * grbm / _XCDS))
+            if coex:
+                line += " valu_coexec=%.0f%%" % (100 * coex / busy)
+        valu, trans, lds = mean(v, "SQ_INSTS_VALU"), mean(v, "SQ_INSTS_VALU_TRANS_F32"), mean(v, "SQ_INSTS_LDS")
+        if valu and trans is not None and lds:
+            line += " per_mfma: valu=%.2f exp=%.2f lds=%.2f" % ((valu - n_mfma - trans) / n_mfma, trans / n_mfma,
+                                                              lds / n_mfma)
+        w = sq2.get(k) if sq2 else None
+        if w and mean(w, "SQ_WAVE_CYCLES"):
+            wc = mean(w, "SQ_WAVE_CYCLES")
+            for tag, c in (("s_waitcnt", "SQ_WAIT_ANY"), ("issue_wait", "SQ_WAIT_INST_ANY"),
+                           ("lds_issue_wait", "SQ_WAIT_INST_LDS")):
+                if mean(w, c) is not None:
+                    line += " %s=%.0f%%" % (tag, 100 * mean(w, c) / wc)
+        out.append(line)
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
-    for a in ("kt", "fetch", "write", "sq"):
+    for a in ("kt", "fetch", "write", "sq", "sq2"):
         ap.add_argument("--" + a)
     ap.add_argument("--prefix", default="p")
     args = ap.parse_args()
@@ -106,8 +148,14 @@ def main():
         out += counter_table("write", w)
     if f is not None and w is not None:
         out += traffic_lines(f, w)
-    if args.sq:
-        out += counter_table("sq", counters(args.sq, args.prefix))
+    sq = counters(args.sq, args.prefix) if args.sq else None
+    sq2 = counters(args.sq2, args.prefix) if args.sq2 else None
+    if sq is not None:
+        out += counter_table("sq", sq)
+    if sq2 is not None:
+        out += counter_table("sq2", sq2)
+    if args.kt and sq is not None:
+        out += derived_lines(args.kt, args.prefix, sq, sq2)
     print("\n".join(out))
 
 
