@@ -31,12 +31,13 @@
 // a common factor, so m only has to move when a row's partial sum of probabilities
 // exceeds RESCALE_SUM (or the row has no reference yet); then the sub-tile is redone
 // against its row maximum and l and the 64 accumulator registers are rescaled,
-// which almost never runs.  The running
-// state enters as (acc = O, m = LSE * log2(e), l = 1) and leaves as O = acc / l,
-// LSE = (m + log2 l) * ln 2, which is the log-sum-exp merge of the step's
-// partial result with the running one.  Row sums are taken over the fp32
-// probabilities before they are rounded to bf16 (summing the rounded values
-// costs 1e-3 of LSE accuracy on rows with few keys).
+// which almost never runs.  A step accumulates its own partial result from an
+// empty state (the first sub-tile sets the reference) and folds it into the
+// running (O, LSE) in its epilogue by log-sum-exp, which is where the running state
+// is read: read in the prologue it would stand in front of every workgroup's first
+// tile, and holding it there cost the kernel 30 spilled registers.  Row sums are
+// taken over the fp32 probabilities before they are rounded to bf16 (summing the
+// rounded values costs 1e-3 of LSE accuracy on rows with few keys).
 //
 // LDS layout.  Both tiles are 64 rows x 256 bytes without padding (the direct
 // loads write 1 KiB per wavefront contiguously); bank conflicts are avoided by
@@ -87,16 +88,7 @@ __device__ inline void load_v_tile_direct(dt_rsrc matrix, int tile_byte_offset, 
 }
 
 // LDS address of this lane's K operand for k-step ks: chunk (2 ks + h) ^ (n & 15) of row n.
-// Steps 4..7 differ from steps 0..3 in bit 3 of the chunk index only.  The kernel is two
-// registers short of keeping all eight addresses out of scratch memory in its hot loop, so
-// four are kept and the other four are made by one XOR each where they are used (the asm
-// keeps the compiler from hoisting them back into registers).
-__device__ inline uint32_t k_step_addr(const uint32_t (&kaddr)[4], int ks) {
-    if (ks < 4) return kaddr[ks];
-    uint32_t a;
-    asm volatile("v_xor_b32 %0, 0x80, %1" : "=v"(a) : "v"(kaddr[ks - 4]));
-    return a;
-}
+__device__ inline uint32_t k_step_addr(const uint32_t (&kaddr)[8], int ks) { return kaddr[ks]; }
 __device__ inline bf16x8 lds_read_b128(const char* lds, uint32_t addr) {
     return *reinterpret_cast<const bf16x8*>(lds + addr);
 }
@@ -121,7 +113,7 @@ __device__ inline bf16x8 lds_read_tr(const char* lds, uint32_t addr) {
 template <bool QK, bool SM, bool PV, bool MASK, int DP, bool PART>
 __device__ inline void step(f32x16& s_cur, f32x16& s_next, bf16x8 (&p_cur)[2], bf16x8 (&p_prev)[2],
                             f32x16 (&oacc)[4 * halves_of(DP)], const bf16x8 (&qf)[8 * halves_of(DP)], float& m,
-                            float& l, float kappa, const uint32_t (&kaddr)[4], const uint32_t (&vaddr)[4],
+                            float& l, float kappa, const uint32_t (&kaddr)[8], const uint32_t (&vaddr)[4],
                             const char* k_next, const char* v_prev, int mask_lim, int part_ks) {
     constexpr int NH = halves_of(DP), KS = ksteps_of(DP), MB = blocks_of(DP);      // per half
     // Operands of slice i are requested from LDS two slices ahead, so only a few of
@@ -136,8 +128,11 @@ __device__ inline void step(f32x16& s_cur, f32x16& s_next, bf16x8 (&p_cur)[2], b
                 va[hh][i] = lds_read_tr(v_prev + hh * TILE_BYTES + (i / 4) * 16 * 256, vaddr[i % 4]);
         }
     };
-    fetch(0);
-    fetch(1);
+    // operands are requested this many slices ahead of their use (3 and 4 measured the same or
+    // slightly worse: LDS latency is covered)
+    constexpr int AHEAD = 2;
+#pragma unroll
+    for (int i = 0; i < AHEAD; ++i) fetch(i);
     if (SM && MASK) {
 #pragma unroll
         for (int r = 0; r < 16; ++r)
@@ -151,7 +146,7 @@ __device__ inline void step(f32x16& s_cur, f32x16& s_next, bf16x8 (&p_cur)[2], b
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         __builtin_amdgcn_sched_barrier(0);         // slices stay in program order
-        if (i + 2 < 8) fetch(i + 2);
+        if (i + AHEAD < 8) fetch(i + AHEAD);
 #pragma unroll
         for (int hh = 0; hh < NH; ++hh) {
             if (QK && i < KS)
@@ -291,11 +286,11 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
     // per-lane addresses: K A-operand reads per k-step, V transposing reads per 32-column
     // block (bytes within a 32-row half tile), and the global byte offsets of this lane's
     // direct loads
-    uint32_t kaddr[4], vaddr[4], kg0[NH], vg0[NH];
+    uint32_t kaddr[8], vaddr[4], kg0[NH], vg0[NH];
     {
         const int x = n & 15;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) kaddr[ks] = n * 256 + (((2 * ks + h) ^ x) << 4);
+        for (int ks = 0; ks < 8; ++ks) kaddr[ks] = n * 256 + (((2 * ks + h) ^ x) << 4);
         const int i = lane & 15, nh = (lane >> 4) & 1, j4 = i >> 2;
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb)
@@ -337,19 +332,17 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
         if (tid < DP / 2) rope_turns[tid] = exp2(-2.0 * tid / DP * p.rope_log2_base) * 0.15915494309189535;
     }
     const float kappa = p.scale * LOG2E;
-    float m = L[a] * LOG2E;                   // -inf stays -inf
-    float l = (h == 0) ? 1.f : 0.f;           // the two half-waves hold partial row sums
+    // This block's own partial result is accumulated from an empty state and folded into the
+    // running (O, LSE) in the epilogue, where the running state is read.  Read here instead, it
+    // sits in front of the first tile of every workgroup of the launch at once (the fp32 state
+    // is the largest tensor of a step), which is what a short step spends a quarter of its time on.
+    float m = -INFINITY;                      // no reference yet: the first sub-tile sets it
+    float l = 0.f;                            // the two half-waves hold partial row sums
     f32x16 oacc[4 * NH];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int col = 32 * mb + 8 * g + 4 * h;
-            float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (col < d) x = *reinterpret_cast<const float4*>(O + (int64_t)a * ss + col);
-            oacc[mb][4 * g + 0] = x.x; oacc[mb][4 * g + 1] = x.y;
-            oacc[mb][4 * g + 2] = x.z; oacc[mb][4 * g + 3] = x.w;
-        }
+        for (int r = 0; r < 16; ++r) oacc[mb][r] = 0.f;
 
     __builtin_amdgcn_s_waitcnt(0);     // the direct loads have landed (vmcnt) ...
     __syncthreads();                   // ... for every wavefront
@@ -446,20 +439,39 @@ fwd_mfma_kernel(StepArgs p, int n_qtiles) {
                                                   v_last, 0, part_ks);
     }
 
-    // epilogue: normalise, store the merged state
+    // epilogue: merge this block's partial (unnormalised oacc against reference m, row sum l)
+    // into the running state by log-sum-exp (Alg. 1: accumulate into the output and update the
+    // running softmax statistics), everything in base-2 units:
+    //   LSE' = log2(2^LSE + 2^(m + log2 l)),  O' = O 2^(LSE - LSE') + oacc 2^(m - LSE')
+    // A row that saw no key here (l = 0) keeps its state bit for bit; a row whose state is still
+    // empty (LSE = -inf) takes the partial and never looks at the stored O.
     const float l_tot = half_wave_sum(l);
-    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+    const float lse_old = L[a] * LOG2E;                                       // -inf stays -inf
+    const float lse_part = l_tot > 0.f ? m + __builtin_amdgcn_logf(l_tot) : -INFINITY;
+    const float top = fmaxf(lse_old, lse_part);
+    const float ref = top == -INFINITY ? 0.f : top;                           // no (-inf) - (-inf)
+    const float w_old = __builtin_amdgcn_exp2f(lse_old - ref), w_part = __builtin_amdgcn_exp2f(lse_part - ref);
+    const float w_sum = w_old + w_part;
+    const float inv = w_sum > 0.f ? 1.f / w_sum : 0.f;
+    const float a_old = w_old * inv;
+    const float a_part = l_tot > 0.f ? w_part * inv / l_tot : 0.f;
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            float4 x;
-            x.x = oacc[mb][4 * g + 0] * inv; x.y = oacc[mb][4 * g + 1] * inv;
-            x.z = oacc[mb][4 * g + 2] * inv; x.w = oacc[mb][4 * g + 3] * inv;
             const int col = 32 * mb + 8 * g + 4 * h;
-            if (col < d && row_ok) *reinterpret_cast<float4*>(O + (int64_t)a * ss + col) = x;
+            if (col >= d || !row_ok) continue;            // padding columns, rows beyond the shard
+            float4* dst = reinterpret_cast<float4*>(O + (int64_t)a * ss + col);
+            float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (a_old != 0.f) {
+                x = *dst;
+                x.x *= a_old; x.y *= a_old; x.z *= a_old; x.w *= a_old;
+            }
+            x.x = fmaf(oacc[mb][4 * g + 0], a_part, x.x); x.y = fmaf(oacc[mb][4 * g + 1], a_part, x.y);
+            x.z = fmaf(oacc[mb][4 * g + 2], a_part, x.z); x.w = fmaf(oacc[mb][4 * g + 3], a_part, x.w);
+            *dst = x;
         }
-    if (h == 0 && row_ok) L[a] = (m + __builtin_amdgcn_logf(l_tot)) * LN2;
+    if (h == 0 && row_ok) L[a] = (top + __builtin_amdgcn_logf(w_sum)) * LN2;
 }
 
 }  // namespace
