@@ -147,17 +147,28 @@ __device__ inline void step(f32x16& s_cur, f32x16& s_next, bf16x8 (&p_cur)[2], b
     for (int i = 0; i < 8; ++i) {
         __builtin_amdgcn_sched_barrier(0);         // slices stay in program order
         if (i + AHEAD < 8) fetch(i + AHEAD);
+        // MFMA, one score, MFMA, the other score: a wavefront that issues its MFMAs back to back
+        // waits for the matrix pipeline with its VALU work still ahead of it (+2 % against
+        // both MFMAs first; both exponentials before the second MFMA, or the operand requests
+        // between the two, measured slightly worse)
 #pragma unroll
-        for (int hh = 0; hh < NH; ++hh) {
+        for (int hh = 0; hh < NH; ++hh)
             if (QK && i < KS)
                 s_next = mfma(PART ? zero_beyond_d(ka[hh][i], 8 * hh + i == part_ks) : ka[hh][i], qf[8 * hh + i],
                               s_next);
-            if (PV && i % 4 < MB) oacc[4 * hh + i % 4] = mfma(va[hh][i], p_prev[i / 4], oacc[4 * hh + i % 4]);
-        }
+        __builtin_amdgcn_sched_barrier(0);
+        float p0 = 0.f;
         if (SM) {
-            const float p0 = __builtin_amdgcn_exp2f(fmaf(s_cur[2 * i], kappa, -m));
-            const float p1 = __builtin_amdgcn_exp2f(fmaf(s_cur[2 * i + 1], kappa, -m));
+            p0 = __builtin_amdgcn_exp2f(fmaf(s_cur[2 * i], kappa, -m));
             rs0 += p0;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int hh = 0; hh < NH; ++hh)
+            if (PV && i % 4 < MB) oacc[4 * hh + i % 4] = mfma(va[hh][i], p_prev[i / 4], oacc[4 * hh + i % 4]);
+        __builtin_amdgcn_sched_barrier(0);
+        if (SM) {
+            const float p1 = __builtin_amdgcn_exp2f(fmaf(s_cur[2 * i + 1], kappa, -m));
             rs1 += p1;
             p_cur[i / 4][(2 * i) % 8] = (__bf16)p0;
             p_cur[i / 4][(2 * i) % 8 + 1] = (__bf16)p1;
